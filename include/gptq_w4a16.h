@@ -1,0 +1,133 @@
+/*
+ * gptq_w4a16.h - C ABI of the MI355X (gfx950) W4A16 GPTQ matrix multiply.
+ *
+ * The operation is the 4-bit GPTQ weight-only quantized GEMM that Opt4GPTQ
+ * (arxiv 2511.19438) optimises: Section 3 describes its kernel pipeline (vectorised
+ * activation loads into on-chip memory, packed half-precision multiply-accumulate,
+ * Eq. 14-15, and a hierarchical on-chip reduction before the result is committed,
+ * Eq. 6-10 / Algorithm 1); Section 4.4 states that the result equals the plain GPTQ
+ * computation up to the order of floating point additions.  That plain computation is
+ *
+ *     out[m, n] = sum_k x[m, k] * W[k, n]
+ *     W[k, n]   = scales[r(k), n] * ( q[k, n] - z[r(k), n] )
+ *     q[k, n]   = (u32(qweight[k/8][n]) >> 4*(k%8)) & 15     eight codes per word along K
+ *     z[r, n]   = (u32(qzeros[r][n/8])  >> 4*(n%8)) & 15     eight zero points per word along N
+ *     r(k)      = g_idx ? g_idx[k] : k / group_size          (g_idx: act-order group map)
+ *
+ * Layout.  Every tensor is row-major, contiguous, and lives in DEVICE memory of the
+ * current HIP device.  fp16 is IEEE-754 binary16.
+ *     x        fp16  [M, K]
+ *     qweight  int32 [K/8, N]
+ *     qzeros   int32 [K/group_size, N/8]
+ *     scales   fp16  [K/group_size, N]
+ *     g_idx    int32 [K]  or NULL
+ *     out      fp16  [M, N]
+ *
+ * Ownership.  All pointers are borrowed from the caller; the library neither frees nor
+ * keeps them, except the workspace given to gptq_w4a16_set_workspace(), which it uses
+ * until it is replaced.  Calls only enqueue work on `stream` (a hipStream_t passed as
+ * void*, NULL = the default stream) and never synchronise it: inputs and outputs must
+ * stay alive until the stream has passed the call.
+ *
+ * Errors.  Every entry point returns 0 on success or a negative gptq_status code; it
+ * never throws, aborts or prints.  Nothing is enqueued when an error is returned.
+ * A g_idx entry outside [0, K/group_size) is a precondition violation that the library
+ * cannot see without reading device memory; the result is then undefined.
+ *
+ * Supported shapes: M >= 1; K, N multiples of 8; group_size a multiple of 8 that divides K.
+ * Tuned for group_size 128.  All base pointers must be 16-byte aligned.
+ */
+#ifndef GPTQ_W4A16_H
+#define GPTQ_W4A16_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void *gptq_stream_t; /* hipStream_t */
+
+#define GPTQ_API __attribute__((visibility("default")))
+
+enum gptq_status {
+    GPTQ_OK = 0,
+    GPTQ_INVALID_ARG = -1,         /* NULL required pointer, non-positive size, bad plan field */
+    GPTQ_UNSUPPORTED_SHAPE = -2,   /* divisibility rules above violated */
+    GPTQ_MISALIGNED = -3,          /* a base pointer is not 16-byte aligned */
+    GPTQ_HIP_ERROR = -4,           /* a HIP call or a kernel launch failed */
+    GPTQ_WORKSPACE_TOO_SMALL = -5  /* caller-set workspace smaller than gptq_w4a16_workspace_bytes() */
+};
+
+/*
+ * out = x * W (definition above; the whole pipeline of Section 3: unpack, group lookup,
+ * dequantise, stage activations on chip, contract, reduce the split-K partial sums on
+ * chip and across workgroups, round once to fp16, store).  `out` is OVERWRITTEN and need
+ * not be zeroed (unlike the accumulate-by-atomicAdd contract of Eq. 9-10).
+ * M <= 16 runs the bandwidth-bound split-K vector kernel, larger M the fp16 MFMA kernel.
+ * Accumulation is in fp32; the result differs from the exact sum by fp32 reassociation
+ * and the final fp16 rounding only.  The same inputs give bit-identical outputs on every
+ * call (no floating point atomics are used).
+ */
+GPTQ_API int gptq_w4a16_gemm(const void *x, const void *qweight, const void *qzeros, const void *scales,
+                    const void *g_idx, void *out, int M, int K, int N, int group_size,
+                    gptq_stream_t stream);
+
+/*
+ * Launch plan for gptq_w4a16_gemm_plan(): selects the kernel and its decomposition
+ * explicitly (for tuning sweeps).  A zero field means "let the library choose".
+ */
+typedef struct gptq_w4a16_plan {
+    int kernel;      /* 0 auto, 1 vector split-K kernel (any M, processed 16 rows at a time), 2 MFMA kernel */
+    int split_k;     /* number of K slices (vector kernel); 0 auto */
+    int tile;        /* vector kernel: columns per workgroup (64, 128 or 256);
+                        MFMA kernel: tile id 1..6 = (rows x columns per workgroup) 256x256, 256x128,
+                        128x128, 128x256, 64x128, 32x256; 0 auto */
+    int flags;       /* must be zero */
+    int reserved[4]; /* must be zero */
+} gptq_w4a16_plan_t;
+
+/* Same operation and contract as gptq_w4a16_gemm with an explicit plan (NULL = automatic). */
+GPTQ_API int gptq_w4a16_gemm_plan(const void *x, const void *qweight, const void *qzeros, const void *scales,
+                         const void *g_idx, void *out, int M, int K, int N, int group_size,
+                         gptq_stream_t stream, const gptq_w4a16_plan_t *plan);
+
+/*
+ * The dequantised weights themselves: w_out (fp16 [K, N], device) = W as defined above,
+ * computed as the exact integer difference q - z followed by ONE IEEE fp16 multiplication
+ * by the scale (round to nearest even, subnormals kept).  Bit-exact by definition.
+ */
+GPTQ_API int gptq_w4a16_dequant(const void *qweight, const void *qzeros, const void *scales, const void *g_idx,
+                       void *w_out, int K, int N, int group_size, gptq_stream_t stream);
+
+/*
+ * The unpacked 4-bit fields: q_out (uint8 [K, N], device) = q; z_out (uint8 [K/group_size, N],
+ * device, may be NULL to skip) = z.  Integer work, bit-exact.
+ */
+GPTQ_API int gptq_w4a16_unpack(const void *qweight, void *q_out, const void *qzeros, void *z_out, int K, int N,
+                      int group_size, gptq_stream_t stream);
+
+/*
+ * Split-K scratch.  gptq_w4a16_gemm needs device scratch for the partial sums of the K
+ * slices and one arrival counter per column tile.  gptq_w4a16_workspace_bytes() is an
+ * upper bound for a given problem (0 for invalid shapes).  If the caller never sets a
+ * workspace the library allocates one with hipMalloc on first use and grows it when
+ * needed (the only allocation it makes; growing synchronises the device).
+ * gptq_w4a16_set_workspace() hands over caller-owned device memory (256-byte aligned)
+ * instead; it clears the counter area with a synchronous hipMemset.  Passing NULL returns
+ * to library-owned scratch.  There is one workspace per process: calls that overlap in
+ * time on different streams race on it.
+ */
+GPTQ_API size_t gptq_w4a16_workspace_bytes(int M, int K, int N, int group_size);
+GPTQ_API int gptq_w4a16_set_workspace(void *dev_ptr, size_t bytes);
+
+/* Text for a status code (static storage). */
+GPTQ_API const char *gptq_w4a16_strerror(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+GPTQ_API int gptq_w4a16_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GPTQ_W4A16_H */

@@ -1,0 +1,58 @@
+// Instantiates the split-K vector kernel for ONE batch size (GPTQ_DECODE_MB, set on the
+// compiler command line: 1, 2, 4, 8 or 16) so that the five sizes compile in parallel.
+#include "decode_kernel.h"
+
+#ifndef GPTQ_DECODE_MB
+#error "compile with -DGPTQ_DECODE_MB=<1|2|4|8|16>"
+#endif
+
+namespace gptq {
+namespace decode {
+
+namespace {
+
+template <int MB, int LPR, int R, bool ACT>
+hipError_t launch_one(const Args &a, size_t lds_bytes, hipStream_t stream)
+{
+    auto kernel = decode_kernel<MB, LPR, R, ACT>;
+    if (lds_bytes > 48 * 1024) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (err != hipSuccess)
+            return err;
+    }
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.tiles_n * a.split_k)), dim3(kThreads), lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+template <>
+hipError_t launch_mb<GPTQ_DECODE_MB>(const Args &a, int lpr, int chunk_rows, bool act, size_t lds_bytes,
+                                     hipStream_t stream)
+{
+    constexpr int MB = GPTQ_DECODE_MB;
+    if (act) {
+        if (lpr == 16 && chunk_rows == 4)
+            return launch_one<MB, 16, 4, true>(a, lds_bytes, stream);
+        return hipErrorInvalidValue;
+    }
+    if (chunk_rows == 4) {
+        switch (lpr) {
+        case 16: return launch_one<MB, 16, 4, false>(a, lds_bytes, stream);
+        case 32: return launch_one<MB, 32, 4, false>(a, lds_bytes, stream);
+        case 64: return launch_one<MB, 64, 4, false>(a, lds_bytes, stream);
+        default: return hipErrorInvalidValue;
+        }
+    }
+    if (lpr != 16)
+        return hipErrorInvalidValue;
+    if (chunk_rows == 2)
+        return launch_one<MB, 16, 2, false>(a, lds_bytes, stream);
+    if (chunk_rows == 1)
+        return launch_one<MB, 16, 1, false>(a, lds_bytes, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace decode
+}  // namespace gptq

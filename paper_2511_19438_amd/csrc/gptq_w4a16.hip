@@ -1,0 +1,257 @@
+// C-ABI entry points of the W4A16 GPTQ library: argument validation, kernel choice, scratch.
+// The contract of every function is stated in include/gptq_w4a16.h.
+#include "gptq_w4a16.h"
+
+#include <mutex>
+
+#include "kernels.h"
+
+namespace {
+
+using namespace gptq;
+
+constexpr int kVersion = 100;  // 0.1.0
+constexpr int kMaxDevices = 16;
+constexpr int kDecodeMaxM = 16;
+
+struct Workspace {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+    bool owned = false;
+};
+
+std::mutex g_mutex;
+Workspace g_ws[kMaxDevices];
+
+bool aligned16(const void *p)
+{
+    return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
+}
+
+int check_shape(int K, int N, int group_size)
+{
+    if (K <= 0 || N <= 0 || group_size <= 0)
+        return GPTQ_INVALID_ARG;
+    if (K % 8 || N % 8 || group_size % 8 || K % group_size)
+        return GPTQ_UNSUPPORTED_SHAPE;
+    // element counts must fit the 32-bit index arithmetic of the kernels' row/column numbers
+    if ((long long)K * N > (1LL << 40))
+        return GPTQ_UNSUPPORTED_SHAPE;
+    return GPTQ_OK;
+}
+
+// Makes sure the current device has scratch of at least `bytes`; returns it in *out.
+int acquire_workspace(size_t bytes, void **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return GPTQ_HIP_ERROR;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    Workspace &ws = g_ws[dev];
+    if (ws.ptr && ws.bytes >= bytes) {
+        *out = ws.ptr;
+        return GPTQ_OK;
+    }
+    if (ws.ptr && !ws.owned)
+        return GPTQ_WORKSPACE_TOO_SMALL;
+    // library-owned scratch: grow.  Earlier launches may still use the old block, so drain the device first.
+    if (ws.ptr) {
+        if (hipDeviceSynchronize() != hipSuccess)
+            return GPTQ_HIP_ERROR;
+        (void)hipFree(ws.ptr);
+        ws = Workspace();
+    }
+    size_t want = bytes + bytes / 2;
+    if (want < (size_t)(8u << 20))
+        want = (size_t)(8u << 20);
+    void *p = nullptr;
+    if (hipMalloc(&p, want) != hipSuccess)
+        return GPTQ_HIP_ERROR;
+    // the arrival counters live at the front and must start at zero; clear everything once
+    if (hipMemset(p, 0, want) != hipSuccess) {
+        (void)hipFree(p);
+        return GPTQ_HIP_ERROR;
+    }
+    ws.ptr = p;
+    ws.bytes = want;
+    ws.owned = true;
+    *out = p;
+    return GPTQ_OK;
+}
+
+int run_gemm(const Problem &p, hipStream_t stream, const gptq_w4a16_plan_t *plan)
+{
+    int kernel = plan ? plan->kernel : 0;
+    if (kernel == 0)
+        kernel = (p.M <= kDecodeMaxM) ? 1 : 2;
+    if (kernel == 2 && !prefill_supported(p))
+        kernel = 1;
+
+    if (kernel == 1) {
+        DecodePlan dp;
+        dp.cols_per_wg = plan ? plan->tile : 0;
+        dp.split_k = plan ? plan->split_k : 0;
+        dp.chunk_rows = 0;
+        dp.chunks_per_slice = 0;
+        dp.flags = 0;
+        decode_make_plan(p, dp);
+        void *ws = nullptr;
+        const int rc = acquire_workspace(decode_workspace_bytes(p, dp), &ws);
+        if (rc != GPTQ_OK)
+            return rc;
+        return launch_decode(p, dp, ws, stream) == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
+    }
+    PrefillPlan pp;
+    pp.tile = plan ? plan->tile : 0;
+    prefill_make_plan(p, pp);
+    return launch_prefill(p, pp, stream) == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gptq_w4a16_gemm_plan(const void *x, const void *qweight, const void *qzeros, const void *scales,
+                         const void *g_idx, void *out, int M, int K, int N, int group_size,
+                         gptq_stream_t stream, const gptq_w4a16_plan_t *plan)
+{
+    if (!x || !qweight || !qzeros || !scales || !out || M <= 0)
+        return GPTQ_INVALID_ARG;
+    const int rc = check_shape(K, N, group_size);
+    if (rc != GPTQ_OK)
+        return rc;
+    if (plan) {
+        if (plan->kernel < 0 || plan->kernel > 2 || plan->split_k < 0 || plan->tile < 0 || plan->flags != 0)
+            return GPTQ_INVALID_ARG;
+        for (int i = 0; i < 4; ++i)
+            if (plan->reserved[i] != 0)
+                return GPTQ_INVALID_ARG;
+    }
+    if (!aligned16(x) || !aligned16(qweight) || !aligned16(qzeros) || !aligned16(scales) || !aligned16(out) ||
+        (g_idx && !aligned16(g_idx)))
+        return GPTQ_MISALIGNED;
+    Problem p;
+    p.x = static_cast<const half_t *>(x);
+    p.qweight = static_cast<const uint32_t *>(qweight);
+    p.qzeros = static_cast<const uint32_t *>(qzeros);
+    p.scales = static_cast<const half_t *>(scales);
+    p.g_idx = static_cast<const int32_t *>(g_idx);
+    p.out = static_cast<half_t *>(out);
+    p.M = M;
+    p.K = K;
+    p.N = N;
+    p.group_size = group_size;
+    return run_gemm(p, static_cast<hipStream_t>(stream), plan);
+}
+
+int gptq_w4a16_gemm(const void *x, const void *qweight, const void *qzeros, const void *scales,
+                    const void *g_idx, void *out, int M, int K, int N, int group_size, gptq_stream_t stream)
+{
+    return gptq_w4a16_gemm_plan(x, qweight, qzeros, scales, g_idx, out, M, K, N, group_size, stream, nullptr);
+}
+
+int gptq_w4a16_dequant(const void *qweight, const void *qzeros, const void *scales, const void *g_idx,
+                       void *w_out, int K, int N, int group_size, gptq_stream_t stream)
+{
+    if (!qweight || !qzeros || !scales || !w_out)
+        return GPTQ_INVALID_ARG;
+    const int rc = check_shape(K, N, group_size);
+    if (rc != GPTQ_OK)
+        return rc;
+    if (!aligned16(qweight) || !aligned16(qzeros) || !aligned16(scales) || !aligned16(w_out) ||
+        (g_idx && !aligned16(g_idx)))
+        return GPTQ_MISALIGNED;
+    const hipError_t err = launch_dequant(static_cast<const uint32_t *>(qweight), static_cast<const uint32_t *>(qzeros),
+                                          static_cast<const half_t *>(scales), static_cast<const int32_t *>(g_idx),
+                                          static_cast<half_t *>(w_out), K, N, group_size,
+                                          static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
+}
+
+int gptq_w4a16_unpack(const void *qweight, void *q_out, const void *qzeros, void *z_out, int K, int N,
+                      int group_size, gptq_stream_t stream)
+{
+    if (!qweight || !q_out || (z_out && !qzeros))
+        return GPTQ_INVALID_ARG;
+    const int rc = check_shape(K, N, group_size);
+    if (rc != GPTQ_OK)
+        return rc;
+    if (!aligned16(qweight) || !aligned16(q_out) || (z_out && (!aligned16(qzeros) || !aligned16(z_out))))
+        return GPTQ_MISALIGNED;
+    const hipError_t err =
+        launch_unpack(static_cast<const uint32_t *>(qweight), static_cast<uint8_t *>(q_out),
+                      static_cast<const uint32_t *>(qzeros), static_cast<uint8_t *>(z_out), K, N, group_size,
+                      static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
+}
+
+size_t gptq_w4a16_workspace_bytes(int M, int K, int N, int group_size)
+{
+    if (M <= 0 || check_shape(K, N, group_size) != GPTQ_OK)
+        return 0;
+    // The automatic plan never uses more slices than this bound; explicit plans are checked at launch.
+    Problem p = {};
+    p.M = M;
+    p.K = K;
+    p.N = N;
+    p.group_size = group_size;
+    DecodePlan dp = {};
+    decode_make_plan(p, dp);
+    size_t bytes = decode_workspace_bytes(p, dp);
+    // act-order problems may be planned with a different slice count
+    int dummy = 0;
+    p.g_idx = &dummy;
+    DecodePlan da = {};
+    decode_make_plan(p, da);
+    const size_t act = decode_workspace_bytes(p, da);
+    return bytes > act ? bytes : act;
+}
+
+int gptq_w4a16_set_workspace(void *dev_ptr, size_t bytes)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return GPTQ_HIP_ERROR;
+    if (dev_ptr && (reinterpret_cast<uintptr_t>(dev_ptr) & 255u) != 0)
+        return GPTQ_MISALIGNED;
+    if (dev_ptr && bytes < 4096)
+        return GPTQ_WORKSPACE_TOO_SMALL;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    Workspace &ws = g_ws[dev];
+    if (ws.ptr && ws.owned) {
+        if (hipDeviceSynchronize() != hipSuccess)
+            return GPTQ_HIP_ERROR;
+        (void)hipFree(ws.ptr);
+    }
+    ws = Workspace();
+    if (dev_ptr) {
+        if (hipDeviceSynchronize() != hipSuccess)
+            return GPTQ_HIP_ERROR;
+        if (hipMemset(dev_ptr, 0, bytes) != hipSuccess)
+            return GPTQ_HIP_ERROR;
+        ws.ptr = dev_ptr;
+        ws.bytes = bytes;
+        ws.owned = false;
+    }
+    return GPTQ_OK;
+}
+
+const char *gptq_w4a16_strerror(int code)
+{
+    switch (code) {
+    case GPTQ_OK: return "ok";
+    case GPTQ_INVALID_ARG: return "invalid argument (null pointer, non-positive size or bad plan)";
+    case GPTQ_UNSUPPORTED_SHAPE: return "unsupported shape (K, N, group_size must be multiples of 8; group_size must divide K)";
+    case GPTQ_MISALIGNED: return "a base pointer is not 16-byte aligned";
+    case GPTQ_HIP_ERROR: return "a HIP call or kernel launch failed";
+    case GPTQ_WORKSPACE_TOO_SMALL: return "caller-set workspace is too small for this problem";
+    default: return "unknown status code";
+    }
+}
+
+int gptq_w4a16_version(void)
+{
+    return kVersion;
+}
+
+}  // extern "C"

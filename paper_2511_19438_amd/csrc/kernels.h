@@ -1,0 +1,56 @@
+// Internal launcher interface between the C-ABI translation unit and the kernel files.
+// Everything here is device-pointer based; shapes were validated by the caller.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gptq {
+
+using half_t = _Float16;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+struct Problem {
+    const half_t *x;          // [M, K]
+    const uint32_t *qweight;  // [K/8, N]
+    const uint32_t *qzeros;   // [K/group, N/8]
+    const half_t *scales;     // [K/group, N]
+    const int32_t *g_idx;     // [K] or nullptr
+    half_t *out;              // [M, N]
+    int M, K, N, group_size;
+};
+
+// ---- unpack / dequant (standalone, HBM-bound) ----
+hipError_t launch_unpack(const uint32_t *qweight, uint8_t *q_out, const uint32_t *qzeros, uint8_t *z_out, int K,
+                         int N, int group_size, hipStream_t stream);
+hipError_t launch_dequant(const uint32_t *qweight, const uint32_t *qzeros, const half_t *scales,
+                          const int32_t *g_idx, half_t *w_out, int K, int N, int group_size, hipStream_t stream);
+
+// ---- decode: split-K vector kernel, M <= 16 per launch ----
+struct DecodePlan {
+    int cols_per_wg;   // 64, 128 or 256
+    int split_k;       // number of K slices
+    int chunk_rows;    // packed rows handled per lane per step (1, 2 or 4), divides group_size/8
+    int chunks_per_slice;
+    int flags;
+};
+// Fills `plan` (honouring non-zero requests in it) for the problem.
+void decode_make_plan(const Problem &p, DecodePlan &plan);
+// Bytes of scratch (partials + counters) the plan needs; counter area comes first.
+size_t decode_workspace_bytes(const Problem &p, const DecodePlan &plan);
+size_t decode_counter_bytes(int N);
+hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspace, hipStream_t stream);
+
+// ---- prefill: fp16 MFMA kernel ----
+struct PrefillPlan {
+    int tile;  // tile configuration id (1-based), 0 = auto
+};
+bool prefill_supported(const Problem &p);
+void prefill_make_plan(const Problem &p, PrefillPlan &plan);
+hipError_t launch_prefill(const Problem &p, const PrefillPlan &plan, hipStream_t stream);
+
+}  // namespace gptq

@@ -1,0 +1,69 @@
+// Instantiates the MFMA kernel for ONE tile configuration (GPTQ_PREFILL_TILE, set on the compiler
+// command line) so that the configurations compile in parallel.
+#include "prefill_kernel.h"
+
+#ifndef GPTQ_PREFILL_TILE
+#error "compile with -DGPTQ_PREFILL_TILE=<1..6>"
+#endif
+
+namespace gptq {
+namespace prefill {
+
+template <int TILE>
+hipError_t launch_tile(const Args &a, int mode, hipStream_t stream);
+
+namespace {
+
+#if GPTQ_PREFILL_TILE == 1
+constexpr int BM = 256, BN = 256, WM = 1, WN = 4;
+#elif GPTQ_PREFILL_TILE == 2
+constexpr int BM = 256, BN = 128, WM = 2, WN = 2;
+#elif GPTQ_PREFILL_TILE == 3
+constexpr int BM = 128, BN = 128, WM = 2, WN = 2;
+#elif GPTQ_PREFILL_TILE == 4
+constexpr int BM = 128, BN = 256, WM = 1, WN = 4;
+#elif GPTQ_PREFILL_TILE == 5
+constexpr int BM = 64, BN = 128, WM = 1, WN = 4;
+#elif GPTQ_PREFILL_TILE == 6
+constexpr int BM = 32, BN = 256, WM = 1, WN = 4;
+#else
+#error "unknown tile id"
+#endif
+
+template <int MODE>
+hipError_t launch_mode(Args a, hipStream_t stream)
+{
+    a.tiles_m = (a.M + BM - 1) / BM;
+    a.tiles_n = (a.N + BN - 1) / BN;
+    const int total = a.tiles_m * a.tiles_n;
+    const unsigned grid = 8u * (unsigned)((total + 7) / 8);
+    const size_t lds = 2 * (size_t)BM * BK * sizeof(half_t);
+    auto kernel = prefill_kernel<BM, BN, WM, WN, MODE>;
+    if (lds > 48 * 1024) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (err != hipSuccess)
+            return err;
+    }
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), lds, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+template <>
+hipError_t launch_tile<GPTQ_PREFILL_TILE>(const Args &a, int mode, hipStream_t stream)
+{
+    if (mode == kGroupPerStage)
+        return launch_mode<kGroupPerStage>(a, stream);
+#if GPTQ_PREFILL_TILE == 3
+    if (mode == kGroupPerRow)
+        return launch_mode<kGroupPerRow>(a, stream);
+    if (mode == kActOrder)
+        return launch_mode<kActOrder>(a, stream);
+#endif
+    return hipErrorInvalidValue;
+}
+
+}  // namespace prefill
+}  // namespace gptq

@@ -1,0 +1,285 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Bars: unpack and dequant bit-exact; GEMM within 2e-2 * max(1, |ref|) of the fp64-accumulated
+reference on every element (and far inside it: fp32 accumulation should sit near one fp16 ulp).
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle  # noqa: E402
+from paper_2511_19438_amd import workloads  # noqa: E402
+
+TOL = 2e-2
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2511_19438_amd import binding
+
+    binding.load()  # raises if the HIP library is not built: there is no fallback to test
+    return binding
+
+
+def dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run_gemm(B, case, group, plan=None):
+    x, qw, qz, sc, gi = (dev(case[k]) for k in ("x", "qweight", "qzeros", "scales", "g_idx"))
+    out = torch.full((x.shape[0], qw.shape[1]), float("nan"), dtype=torch.float16, device="cuda")
+    B.gptq_w4a16_gemm(x, qw, qz, sc, gi, out, group, plan)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def assert_within_band(out, ref, what, tight=0.25):
+    out64 = out.astype(np.float64)
+    assert np.all(np.isfinite(out64)), f"{what}: non-finite output"
+    ratio = np.abs(out64 - ref) / (TOL * np.maximum(1.0, np.abs(ref)))
+    worst = float(ratio.max())
+    assert worst <= 1.0, f"{what}: max err/tol = {worst:.3f} at {np.unravel_index(ratio.argmax(), ratio.shape)}"
+    # fp32 accumulation + one fp16 rounding: a correct kernel uses a small part of the band
+    assert worst <= tight, f"{what}: err/tol = {worst:.3f} is suspiciously large for fp32 accumulation"
+    return worst
+
+
+# ------------------------------------------------------------------ unpack / dequant (bit-exact)
+
+@pytest.mark.parametrize("K,N,group", [(128, 8, 128), (256, 72, 32), (1024, 1000, 128), (4096, 4096, 128), (384, 264, 64)])
+def test_unpack_bit_exact(B, K, N, group):
+    w = workloads.make_weights(K, N, group, seed=K + N)
+    q_out = torch.empty((K, N), dtype=torch.uint8, device="cuda")
+    z_out = torch.empty((K // group, N), dtype=torch.uint8, device="cuda")
+    B.gptq_w4a16_unpack(dev(w["qweight"]), q_out, dev(w["qzeros"]), z_out, group)
+    torch.cuda.synchronize()
+    assert np.array_equal(q_out.cpu().numpy(), oracle.unpack_qweight(w["qweight"]))
+    assert np.array_equal(z_out.cpu().numpy(), oracle.unpack_qzeros(w["qzeros"]))
+    # z_out is optional
+    q2 = torch.empty_like(q_out)
+    B.gptq_w4a16_unpack(dev(w["qweight"]), q2, None, None, group)
+    assert torch.equal(q2, q_out)
+
+
+def test_unpack_hand_packed_words(B):
+    qweight = np.array([[0x76543210, 0xF0000001, 0x8000000F, 0x11111111, 0, 0xFFFFFFFF, 0x0F0F0F0F, 0x12345678]],
+                       np.uint32).view(np.int32)
+    qzeros = np.array([[0xFEDCBA98]], np.uint32).view(np.int32)
+    q_out = torch.empty((8, 8), dtype=torch.uint8, device="cuda")
+    z_out = torch.empty((1, 8), dtype=torch.uint8, device="cuda")
+    B.gptq_w4a16_unpack(dev(qweight), q_out, dev(qzeros), z_out, 8)
+    q = q_out.cpu().numpy()
+    assert q[:, 0].tolist() == [0, 1, 2, 3, 4, 5, 6, 7]
+    assert q[:, 1].tolist() == [1, 0, 0, 0, 0, 0, 0, 15]
+    assert q[:, 2].tolist() == [15, 0, 0, 0, 0, 0, 0, 8]
+    assert q[:, 7].tolist() == [8, 7, 6, 5, 4, 3, 2, 1]
+    assert z_out.cpu().numpy()[0].tolist() == [8, 9, 10, 11, 12, 13, 14, 15]
+
+
+@pytest.mark.parametrize("K,N,group,act", [(128, 8, 128, False), (256, 72, 32, True), (1024, 1000, 128, False),
+                                           (4096, 4096, 128, False), (4096, 11008, 128, True), (384, 264, 8, False),
+                                           (512, 136, 512, True)])
+def test_dequant_bit_exact(B, K, N, group, act):
+    w = workloads.make_weights(K, N, group, seed=K + N + 1, act_order=act)
+    w_out = torch.empty((K, N), dtype=torch.float16, device="cuda")
+    B.gptq_w4a16_dequant(dev(w["qweight"]), dev(w["qzeros"]), dev(w["scales"]), dev(w["g_idx"]), w_out, group)
+    torch.cuda.synchronize()
+    expected = oracle.dequant(w["qweight"], w["qzeros"], w["scales"], w["g_idx"], group)
+    assert np.array_equal(w_out.cpu().numpy().view(np.uint16), expected.view(np.uint16))
+
+
+def test_dequant_subnormal_negative_and_overflowing_scales(B):
+    K, N, group = 64, 16, 32
+    w = workloads.make_weights(K, N, group, seed=3)
+    special = np.array([2.0 ** -24, 2.0 ** -20, 3 * 2.0 ** -24, -0.007, 30000.0, -30000.0, 6.1e-5, 1.0], np.float16)
+    w["scales"] = np.tile(special, (K // group, N // 8)).astype(np.float16)
+    w_out = torch.empty((K, N), dtype=torch.float16, device="cuda")
+    B.gptq_w4a16_dequant(dev(w["qweight"]), dev(w["qzeros"]), dev(w["scales"]), None, w_out, group)
+    expected = oracle.dequant(w["qweight"], w["qzeros"], w["scales"], None, group)
+    assert np.array_equal(w_out.cpu().numpy().view(np.uint16), expected.view(np.uint16))
+
+
+def test_golden_dequant_samples(B):
+    import os
+
+    rows = [l.split() for l in open(os.path.join(os.path.dirname(__file__), "golden", "config0_dequant_samples.txt"))
+            if not l.startswith("#")]
+    w = workloads.make_weights(4096, 4096, 128, seed=workloads.case_seed(0))
+    w_out = torch.empty((4096, 4096), dtype=torch.float16, device="cuda")
+    B.gptq_w4a16_dequant(dev(w["qweight"]), dev(w["qzeros"]), dev(w["scales"]), None, w_out, 128)
+    got = w_out.cpu().numpy().view(np.uint16)
+    for k, n, bits in rows:
+        assert int(got[int(k), int(n)]) == int(bits, 16)
+
+
+# ------------------------------------------------------------------ GEMM, vector (decode) kernel
+
+DECODE_SHAPES = [
+    # (K, N, group, act_order): several column tiles with a ragged last one, several K slices
+    (1024, 200, 128, False),
+    (2048, 1032, 128, False),
+    (1024, 328, 128, True),
+    (768, 136, 64, False),
+    (512, 72, 32, True),
+    (256, 64, 16, False),   # two packed rows per group: chunk of 2
+    (192, 40, 24, False),   # three packed rows per group: chunk of 1
+    (128, 8, 128, False),   # the smallest legal problem
+]
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 13, 16])
+@pytest.mark.parametrize("K,N,group,act", DECODE_SHAPES)
+def test_decode_gemm_matches_oracle(B, M, K, N, group, act):
+    case = workloads.make_case(M, K, N, group, seed=10 * K + N + M, act_order=act)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], case["g_idx"], group)
+    out = run_gemm(B, case, group)
+    assert_within_band(out, ref, f"decode M={M} K={K} N={N} g={group} act={act}")
+
+
+@pytest.mark.parametrize("tile", [64, 128, 256])
+@pytest.mark.parametrize("split_k", [1, 2, 3, 7, 64])
+@pytest.mark.parametrize("M", [1, 4, 16])
+def test_decode_plans_match_oracle(B, tile, split_k, M):
+    K, N, group = 2048, 776, 128
+    case = workloads.make_case(M, K, N, group, seed=77 + M)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    out = run_gemm(B, case, group, B.Plan(kernel=1, split_k=split_k, tile=tile))
+    assert_within_band(out, ref, f"plan tile={tile} split={split_k} M={M}")
+
+
+def test_vector_kernel_handles_batches_above_16(B):
+    M, K, N, group = 37, 512, 136, 128
+    case = workloads.make_case(M, K, N, group, seed=5)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    out = run_gemm(B, case, group, B.Plan(kernel=1))
+    assert_within_band(out, ref, "vector kernel M=37")
+
+
+# ------------------------------------------------------------------ GEMM, MFMA (prefill) kernel
+
+PREFILL_CASES = [
+    # (M, K, N, group, act_order)
+    (17, 256, 72, 128, False),
+    (64, 512, 256, 128, False),
+    (100, 1024, 328, 128, False),
+    (256, 512, 512, 64, False),
+    (300, 768, 264, 128, False),
+    (513, 1024, 520, 128, False),
+    (96, 256, 136, 32, False),    # group per packed row mode
+    (40, 216, 72, 24, False),     # K not a multiple of the 64-wide stage
+    (130, 512, 200, 128, True),   # act-order mode
+    (33, 264, 40, 8, True),
+]
+
+
+@pytest.mark.parametrize("M,K,N,group,act", PREFILL_CASES)
+def test_prefill_gemm_matches_oracle(B, M, K, N, group, act):
+    case = workloads.make_case(M, K, N, group, seed=M + K + N, act_order=act)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], case["g_idx"], group)
+    out = run_gemm(B, case, group)
+    assert_within_band(out, ref, f"prefill M={M} K={K} N={N} g={group} act={act}")
+
+
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("M,N", [(300, 328), (32, 520)])
+def test_prefill_tiles_match_oracle(B, tile, M, N):
+    K, group = 1024, 128
+    case = workloads.make_case(M, K, N, group, seed=tile + M)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    out = run_gemm(B, case, group, B.Plan(kernel=2, tile=tile))
+    assert_within_band(out, ref, f"prefill tile={tile} M={M} N={N}")
+
+
+def test_mfma_kernel_also_serves_small_batches_when_asked(B):
+    M, K, N, group = 3, 512, 264, 128
+    case = workloads.make_case(M, K, N, group, seed=8)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    out = run_gemm(B, case, group, B.Plan(kernel=2))
+    assert_within_band(out, ref, "mfma M=3")
+
+
+# ------------------------------------------------------------------ exactness pins in the GEMM kernels themselves
+
+@pytest.mark.parametrize("M,plan_kernel", [(1, 1), (4, 1), (8, 1), (16, 1), (40, 2), (300, 2)])
+@pytest.mark.parametrize("act", [False, True])
+def test_one_hot_rows_return_weight_rows_bit_exact(B, M, plan_kernel, act):
+    K, N, group = 1024, 264, 128
+    w = workloads.make_weights(K, N, group, seed=9, act_order=act)
+    hot = [(131 * m + 7) % K for m in range(M)]
+    case = dict(w, x=workloads.one_hot_activations(M, K, hot))
+    w16 = oracle.dequant(w["qweight"], w["qzeros"], w["scales"], w["g_idx"], group)
+    out = run_gemm(B, case, group, B.Plan(kernel=plan_kernel))
+    for m, j in enumerate(hot):
+        assert np.array_equal(out[m].view(np.uint16), w16[j].view(np.uint16)), f"row {m} (k={j})"
+
+
+@pytest.mark.parametrize("M", [1, 8, 64])
+def test_dyadic_scales_and_ternary_activations_are_exact(B, M):
+    # scales 2^-7, x in {-1,0,1}: every partial sum is an exact dyadic rational, so fp32 accumulation in any
+    # order equals the fp64 reference and the fp16 result is its single rounding
+    K, N, group = 1024, 328, 128
+    case = workloads.make_weights(K, N, group, seed=12)
+    case["scales"] = np.full_like(case["scales"], 2.0 ** -7)
+    case["x"] = workloads.ternary_activations(M, K, seed=M)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    out = run_gemm(B, case, group)
+    assert np.array_equal(out.view(np.uint16), oracle.double_to_half_bits(ref))
+
+
+@pytest.mark.parametrize("M", [2, 48])
+def test_codes_equal_to_zero_points_give_zero(B, M):
+    K, N, group = 512, 136, 128
+    z = np.random.default_rng(4).integers(0, 16, size=(K // group, N), dtype=np.uint8)
+    case = {"qweight": oracle.pack_qweight(np.repeat(z, group, axis=0)), "qzeros": oracle.pack_qzeros(z),
+            "scales": np.full((K // group, N), 0.01, np.float16), "g_idx": None,
+            "x": workloads.make_activations(M, K, seed=4)}
+    out = run_gemm(B, case, group)
+    assert np.all(out == 0)
+
+
+def test_trivial_g_idx_equals_null_and_calls_are_deterministic(B):
+    M, K, N, group = 4, 1024, 264, 128
+    case = workloads.make_case(M, K, N, group, seed=21)
+    a = run_gemm(B, case, group)
+    b = run_gemm(B, case, group)
+    assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+    case_g = dict(case, g_idx=(np.arange(K) // group).astype(np.int32))
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    assert_within_band(run_gemm(B, case_g, group), ref, "explicit trivial g_idx")
+
+
+def test_caller_owned_workspace(B):
+    M, K, N, group = 8, 2048, 520, 128
+    case = workloads.make_case(M, K, N, group, seed=33)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    need = B.gptq_w4a16_workspace_bytes(M, K, N, group)
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    B.gptq_w4a16_set_workspace(ws)
+    try:
+        assert_within_band(run_gemm(B, case, group), ref, "caller workspace")
+        small = torch.empty(4096, dtype=torch.uint8, device="cuda")
+        B.gptq_w4a16_set_workspace(small)
+        with pytest.raises(B.GptqError) as err:
+            run_gemm(B, case, group, B.Plan(kernel=1, split_k=8))
+        assert err.value.code == -5
+    finally:
+        B.gptq_w4a16_set_workspace(None)
+    assert_within_band(run_gemm(B, case, group), ref, "library workspace again")
+
+
+def test_golden_gemm_samples_config0(B):
+    import os
+
+    rows = [l.split() for l in open(os.path.join(os.path.dirname(__file__), "golden", "config0_gemm_samples.txt"))
+            if not l.startswith("#")]
+    case = workloads.make_case(1, 4096, 4096, 128, seed=workloads.case_seed(0))
+    out = run_gemm(B, case, 128)
+    for m, n, v in rows:
+        ref = float.fromhex(v)
+        assert abs(float(out[int(m), int(n)]) - ref) <= TOL * max(1.0, abs(ref))
