@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A16 GPTQ matrix multiply on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Workload (the decode batch sweep configuration at M = 1, the case the HBM metric is quoted on):
+one "step" is a decode pass over LAYERS distinct Llama-7B-shaped layers, four GEMVs each
+(fused QKV 4096x12288, O 4096x4096, fused gate+up 4096x22016, down 11008x4096; group 128).
+Every layer has its own weights, so the working set (LAYERS x 105 MB) is far larger than the
+256 MB memory-side cache and every launch streams its weights from HBM.  All inputs are
+resident in HBM before the timed region.  value = algorithmic bytes of a step / time of a step.
+
+The same JSON line also carries the prefill half of the metric (fp16 MFMA TFLOP/s at M = 2048
+on the three Llama-7B shapes), the roofline of the dominant kernel of each regime, and the CPU
+oracle timed on this machine's host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_FP16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16, published
+GROUP = 128
+
+
+def algorithmic_bytes(M, K, N, group=GROUP, act_order=False):
+    """Each operand once: packed weights, scales, packed zeros, activations, output (+ g_idx)."""
+    groups = K // group
+    b = K * N // 2 + groups * N * 2 + groups * (N // 8) * 4 + 2 * M * K + 2 * M * N
+    return b + (4 * K if act_order else 0)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=32, help="distinct layers per decode step")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the prefill (MFMA) leg")
+    ap.add_argument("--no-graph", action="store_true", help="launch every kernel eagerly instead of replaying a HIP graph")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    from paper_2511_19438_amd import binding as B
+    from paper_2511_19438_amd import workloads
+
+    B.load()
+    torch.cuda.set_device(0)
+    shapes = workloads.LLAMA_7B
+    M = 1
+
+    # ---- inputs: distinct seeded weights per layer, resident in HBM ----
+    layers = []
+    host_layer0 = None
+    for layer in range(args.layers):
+        mats = []
+        for si, sh in enumerate(shapes):
+            seed = workloads.case_seed(1, si) + 100 * layer
+            w = workloads.make_weights(sh.K, sh.N, GROUP, seed=seed)
+            x = workloads.make_activations(M, sh.K, seed=seed)
+            if layer == 0:
+                host_layer0 = host_layer0 or []
+                host_layer0.append(dict(w, x=x))
+            mats.append({
+                "x": torch.from_numpy(x).cuda(),
+                "qweight": torch.from_numpy(w["qweight"]).cuda(),
+                "qzeros": torch.from_numpy(w["qzeros"]).cuda(),
+                "scales": torch.from_numpy(w["scales"]).cuda(),
+                "out": torch.empty((M, sh.N), dtype=torch.float16, device="cuda"),
+            })
+        layers.append(mats)
+    launches_per_step = args.layers * len(shapes)
+    bytes_per_step = args.layers * sum(algorithmic_bytes(M, sh.K, sh.N) for sh in shapes)
+
+    def step():
+        for mats in layers:
+            for t in mats:
+                B.gptq_w4a16_gemm(t["x"], t["qweight"], t["qzeros"], t["scales"], None, t["out"], GROUP)
+
+    # One step = one HIP graph of all launches (captured once; replaying it removes the host's per-launch
+    # cost, which at 1-10 us per kernel would otherwise be what is measured).  --no-graph launches eagerly.
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        step()  # first call sizes the library's split-K scratch (the only allocation it ever makes)
+        torch.cuda.synchronize()
+        run_step = step
+        if not args.no_graph:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                step()
+            run_step = graph.replay
+        for _ in range(args.warmup):
+            run_step()
+        torch.cuda.synchronize()
+        # events are recorded on the stream the kernels run on
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record(stream)
+        for _ in range(args.steps):
+            run_step()
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    gpu_s = ev0.elapsed_time(ev1) * 1e-3
+    ms_per_step = wall * 1e3 / args.steps
+    value = bytes_per_step * args.steps / wall / 1e9
+
+    # sanity: the timed path computed the right thing (layer 0, smallest shape, against the oracle)
+    import oracle
+
+    chk = host_layer0[1]
+    ref = oracle.gemm_ref(chk["x"], chk["qweight"], chk["qzeros"], chk["scales"], None, GROUP)
+    got = layers[0][1]["out"].cpu().numpy().astype(np.float64)
+    max_ratio = float((np.abs(got - ref) / (2e-2 * np.maximum(1.0, np.abs(ref)))).max())
+    if not max_ratio <= 1.0:
+        print(f"bench.py: GPU result outside the tolerance band (err/tol = {max_ratio})", file=sys.stderr)
+        sys.exit(1)
+
+    # ---- roofline of the dominant kernel: the M=1 vector kernel, averaged over the launches of the timed region ----
+    avg_launch_s = gpu_s / (args.steps * launches_per_step)
+    bytes_per_launch = bytes_per_step / launches_per_step
+    achieved = bytes_per_launch / avg_launch_s / 1e9
+    roofline = {"bound": "hbm", "kernel": "decode_kernel<MB=1> (split-K vector kernel)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch": int(bytes_per_launch), "avg_launch_us": round(avg_launch_s * 1e6, 3)}
+
+    # ---- prefill half of the metric: M = 2048 on the 7B shapes ----
+    prefill = None
+    if not args.no_prefill:
+        prefill = prefill_leg(torch, B, workloads, layers)
+
+    # ---- CPU oracle on this machine's host cores, bounded sample: layer 0 of the same workload ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        reps, spent = 0, 0.0
+        while spent < 10.0 and reps < 50:
+            t = time.perf_counter()
+            for c in host_layer0:
+                oracle.gemm_ref(c["x"], c["qweight"], c["qzeros"], c["scales"], None, GROUP)
+            spent += time.perf_counter() - t
+            reps += 1
+        layer_bytes = sum(algorithmic_bytes(M, sh.K, sh.N) for sh in shapes)
+        cpu = {"value": round(layer_bytes * reps / spent / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(),
+               "kind": "oracle",
+               "sample": f"layer 0 of the step (4 GEMVs, {layer_bytes / 1e6:.1f} MB algorithmic), {reps} repetitions, "
+                         f"{spent:.1f} s"}
+
+    line = {
+        "metric": "W4A16 GEMM: HBM GB/s at M=1 decode; TFLOP/s at M=2048 prefill",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp16 x int4 -> fp32 accumulate", "data": "synthetic",
+        "config": {"workload": f"decode M=1, {args.layers} distinct Llama-7B-shaped layers x "
+                               "{qkv 4096x12288, o 4096x4096, gate_up 4096x22016, down 11008x4096}, group 128",
+                   "launches_per_step": launches_per_step, "algorithmic_bytes_per_step": int(bytes_per_step),
+                   "launch": "eager" if args.no_graph else "hip_graph",
+                   "check_err_over_tol": round(max_ratio, 4)},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    if prefill:
+        line["prefill"] = prefill["summary"]
+        line["roofline_prefill"] = prefill["roofline"]
+    print(json.dumps(line))
+
+
+def prefill_leg(torch, B, workloads, layers, M=2048, reps=15, warm=3):
+    """TFLOP/s of the MFMA kernel at M = 2048 on the three Llama-7B weight shapes of layer 0."""
+    shapes = workloads.LLAMA_7B
+    results = []
+    for si in (0, 2, 3):  # qkv, gate_up, down
+        sh = shapes[si]
+        t = layers[0][si]
+        x = torch.from_numpy(workloads.make_activations(M, sh.K, seed=workloads.case_seed(3, si))).cuda()
+        out = torch.empty((M, sh.N), dtype=torch.float16, device="cuda")
+        for _ in range(warm):
+            B.gptq_w4a16_gemm(x, t["qweight"], t["qzeros"], t["scales"], None, out, GROUP)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            B.gptq_w4a16_gemm(x, t["qweight"], t["qzeros"], t["scales"], None, out, GROUP)
+        e1.record()
+        torch.cuda.synchronize()
+        sec = e0.elapsed_time(e1) * 1e-3 / reps
+        flops = 2.0 * M * sh.K * sh.N
+        results.append({"shape": f"M={M} K={sh.K} N={sh.N}", "us": round(sec * 1e6, 1),
+                        "tflops": round(flops / sec / 1e12, 1)})
+        del x, out
+    total_flops = sum(2.0 * M * shapes[si].K * shapes[si].N for si in (0, 2, 3))
+    total_s = sum(r["us"] for r in results) * 1e-6
+    agg = total_flops / total_s / 1e12
+    dominant = max(results, key=lambda r: r["us"])
+    return {
+        "summary": {"value": round(agg, 1), "unit": "TFLOP/s", "M": M, "shapes": results},
+        "roofline": {"bound": "mfma", "kernel": f"prefill_kernel (fp16 MFMA), {dominant['shape']}",
+                     "achieved": dominant["tflops"], "peak": MFMA_FP16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(dominant["tflops"] / MFMA_FP16_PEAK_TFLOPS, 4), "traffic": None},
+    }
+
+
+if __name__ == "__main__":
+    main()

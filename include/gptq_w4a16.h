@@ -80,9 +80,11 @@ GPTQ_API int gptq_w4a16_gemm(const void *x, const void *qweight, const void *qze
 typedef struct gptq_w4a16_plan {
     int kernel;      /* 0 auto, 1 vector split-K kernel (any M, processed 16 rows at a time), 2 MFMA kernel */
     int split_k;     /* number of K slices (vector kernel); 0 auto */
-    int tile;        /* vector kernel: columns per workgroup (64, 128 or 256);
-                        MFMA kernel: tile id 1..6 = (rows x columns per workgroup) 256x256, 256x128,
-                        128x128, 128x256, 64x128, 32x256; 0 auto */
+    int tile;        /* vector kernel: columns per workgroup (16, 32, 64, 128 or 256);
+                        MFMA kernel: tile id 1..10 = rows x columns per workgroup (wavefront grid):
+                        1 256x256 (1x4), 2 256x128 (2x2), 3 128x128 (2x2), 4 128x256 (1x4, deep ring),
+                        5 64x128 (1x4), 6 32x256 (1x4), 7 256x256 (1x4, 32-k stages), 8 128x256 (1x4),
+                        9 256x256 (2x2), 10 256x256 (2x2, 32-k stages); 0 auto */
     int flags;       /* must be zero */
     int reserved[4]; /* must be zero */
 } gptq_w4a16_plan_t;
@@ -113,8 +115,9 @@ GPTQ_API int gptq_w4a16_unpack(const void *qweight, void *q_out, const void *qze
  * upper bound for a given problem (0 for invalid shapes).  If the caller never sets a
  * workspace the library allocates one with hipMalloc on first use and grows it when
  * needed (the only allocation it makes; growing synchronises the device).
- * gptq_w4a16_set_workspace() hands over caller-owned device memory (256-byte aligned)
- * instead; it clears the counter area with a synchronous hipMemset.  Passing NULL returns
+ * gptq_w4a16_set_workspace() hands over caller-owned device memory (256-byte aligned, at
+ * least gptq_w4a16_workspace_bytes() of the problems it will serve) instead; it clears the
+ * memory with a synchronous hipMemset.  Passing NULL returns
  * to library-owned scratch.  There is one workspace per process: calls that overlap in
  * time on different streams race on it.
  */

@@ -6,6 +6,10 @@ namespace gptq {
 namespace {
 
 constexpr int kMaxSliceLdsBytes = 32 * 1024;  // activations of one slice, all batch rows
+// The arrival counters occupy a fixed area at the front of the scratch, whatever the problem: partial sums of
+// one call must never land where another call keeps counters (they are only ever reset by the kernels).
+constexpr size_t kCounterBytes = 256 * 1024;
+constexpr int kMaxColumnTiles = (int)(kCounterBytes / sizeof(unsigned));
 constexpr size_t kMaxLdsBytes = 160 * 1024;
 
 int batch_template(int M)
@@ -47,36 +51,59 @@ void decode_make_plan(const Problem &p, DecodePlan &plan)
     const bool act = p.g_idx != nullptr;
     const int gr = p.group_size / 8;
     plan.chunk_rows = act ? 4 : (gr % 4 == 0 ? 4 : (gr % 2 == 0 ? 2 : 1));
-    if (plan.cols_per_wg != 64 && plan.cols_per_wg != 128 && plan.cols_per_wg != 256)
+    const bool fixed_shape = act || plan.chunk_rows != 4;  // these variants exist for 64-column tiles only
+    const int c = plan.cols_per_wg;
+    const bool tile_given = (c == 16 || c == 32 || c == 64 || c == 128 || c == 256) && !fixed_shape;
+    if (!tile_given) {
+        // widest tile that still leaves at least ~512 column tiles' worth of workgroups to spread
         plan.cols_per_wg = 64;
-    if (act || plan.chunk_rows != 4)
-        plan.cols_per_wg = 64;
+        if (!fixed_shape) {
+            if (ceil_div(p.N, 64) > 768)
+                plan.cols_per_wg = 128;
+            if (ceil_div(p.N, 128) > 768)
+                plan.cols_per_wg = 256;
+        }
+    }
+    while (!fixed_shape && plan.cols_per_wg < 256 && ceil_div(p.N, plan.cols_per_wg) > kMaxColumnTiles)
+        plan.cols_per_wg *= 2;  // keep one arrival counter per column tile inside the fixed counter area
     const Derived d = derive(p, plan.cols_per_wg, plan.chunk_rows);
 
-    int split = plan.split_k;
-    if (split <= 0) {
-        // Enough workgroups to cover 256 compute units several times, but at least one chunk per row lane.
-        const int target_wgs = act ? 768 : 1024;
-        split = ceil_div(target_wgs, d.tiles_n);
-        const int max_split = ceil_div(d.total_chunks, d.rw);
-        if (split > max_split)
-            split = max_split;
-        if (split < 1)
-            split = 1;
+    const int step_chunks = d.rw * (act ? 1 : 2);  // chunks one workgroup consumes per pipeline step
+    int cps;
+    if (plan.split_k > 0) {
+        int split = plan.split_k < d.total_chunks ? plan.split_k : d.total_chunks;
+        cps = ceil_div(d.total_chunks, split);
+    } else {
+        // Slices are whole pipeline steps (no lane idles or re-reads a clamped chunk) and their number puts
+        // the workgroup count as close as possible (in ratio) to two per compute unit.
+        const double target_wgs = 512.0;
+        int best_cps = 0;
+        double best_cost = 0.0;
+        const int max_steps = ceil_div(d.total_chunks, step_chunks);
+        for (int steps = 1; steps <= max_steps; ++steps) {
+            const int c = steps * step_chunks;
+            if (c > d.max_chunks_per_slice && best_cps)
+                break;
+            const double wgs = (double)d.tiles_n * ceil_div(d.total_chunks, c);
+            const double ratio = wgs > target_wgs ? wgs / target_wgs : target_wgs / wgs;
+            if (!best_cps || ratio < best_cost - 1e-9) {
+                best_cps = c;
+                best_cost = ratio;
+            }
+        }
+        cps = best_cps;
     }
-    if (split > d.total_chunks)
-        split = d.total_chunks;
-    int cps = ceil_div(d.total_chunks, split);
     if (cps > d.max_chunks_per_slice)
         cps = d.max_chunks_per_slice;
+    if (cps < 1)
+        cps = 1;
     plan.chunks_per_slice = cps;
     plan.split_k = ceil_div(d.total_chunks, cps);
 }
 
-size_t decode_counter_bytes(int N)
+size_t decode_counter_bytes(int)
 {
-    const size_t tiles = (size_t)(N + 63) / 64;  // the narrowest tile gives the most counters
-    return (tiles * sizeof(unsigned) + 255) & ~(size_t)255;
+    return kCounterBytes;
 }
 
 size_t decode_workspace_bytes(const Problem &p, const DecodePlan &plan)
@@ -92,6 +119,8 @@ hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspa
 {
     const bool act = p.g_idx != nullptr;
     const Derived d = derive(p, plan.cols_per_wg, plan.chunk_rows);
+    if (d.tiles_n > kMaxColumnTiles)
+        return hipErrorInvalidValue;  // more column tiles than arrival counters (N beyond ~16M columns)
     unsigned char *ws = static_cast<unsigned char *>(workspace);
 
     // batches larger than 16 rows are processed 16 rows at a time on the same stream
@@ -112,6 +141,15 @@ hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspa
         a.N = p.N;
         a.rows = d.rows;
         a.rows_per_group = p.group_size / 8;
+        a.chunk_group_shift = -1;
+        if (a.rows_per_group % plan.chunk_rows == 0) {
+            const int cpg = a.rows_per_group / plan.chunk_rows;
+            if ((cpg & (cpg - 1)) == 0) {
+                a.chunk_group_shift = 0;
+                while ((1 << a.chunk_group_shift) < cpg)
+                    ++a.chunk_group_shift;
+            }
+        }
         a.groups = p.K / p.group_size;
         a.tiles_n = d.tiles_n;
         a.split_k = plan.split_k;
@@ -121,6 +159,8 @@ hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspa
         const int mc = mb < 4 ? mb : 4;
         const int ls = plan.chunks_per_slice * plan.chunk_rows * 8;
         size_t lds = ((size_t)mb * ls * sizeof(half_t) + 15) & ~(size_t)15;
+        if (!act && mb < 8)  // per-chunk sums of the activations (must mirror the kernel's carve-up)
+            lds += ((size_t)mb * plan.chunks_per_slice * 2 * sizeof(float) + 15) & ~(size_t)15;
         lds += (size_t)decode::kWaves * mc * plan.cols_per_wg * sizeof(float);
         if (act)
             lds += (size_t)ls * sizeof(int) + (size_t)a.groups * plan.cols_per_wg * sizeof(uint32_t);

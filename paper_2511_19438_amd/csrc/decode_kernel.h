@@ -5,12 +5,14 @@
 //   * activations are staged in on-chip memory with wide loads (Section 3.2; here 128-bit loads,
 //     and the eight values of a packed row are stored in the order the dequantised pairs need);
 //   * the inner loop is packed half arithmetic (Section 3.3, Eq. 14-15): two weights per VGPR are
-//     formed with one v_and_or_b32, shifted by the zero point with one packed add, and contracted
-//     with v_dot2_f32_f16 into fp32 accumulators;
+//     formed with one v_and_or_b32 and contracted with v_dot2_f32_f16 into fp32 accumulators; zero
+//     point and scale are applied per chunk (small batches) or per element with packed fp16 ops;
 //   * partial sums are reduced on chip before anything is committed (Section 3.1, Eq. 6-10):
 //     across lanes with wavefront shuffles, across wavefronts through LDS, and across the K slices
 //     of different workgroups through fp32 partials in scratch that the last workgroup to arrive
-//     adds in slice order.  No floating point atomics: the result is deterministic.
+//     adds in slice order.  No floating point atomics: the result is deterministic.  The scratch
+//     is written and read with device-scope accesses and an arrival counter, not with device-wide
+//     fences: a fence writes back and invalidates a whole L2 and costs microseconds per workgroup.
 //
 // Work decomposition.  A workgroup (4 wavefronts) owns CT = 4*LPR adjacent columns and one slice
 // of K.  A lane owns 4 adjacent columns (one 128-bit load of a packed qweight row = 4 x 8 weights)
@@ -39,6 +41,7 @@ struct Args {
     int M, K, N;
     int rows;             // K / 8 packed rows
     int rows_per_group;   // group_size / 8
+    int chunk_group_shift;  // log2(chunks per group) if that is a power of two, else -1
     int groups;           // K / group_size
     int tiles_n;
     int split_k;
@@ -62,18 +65,62 @@ __device__ __forceinline__ float dot2(half2_t a, half2_t b, float acc)
     return __builtin_amdgcn_fdot2(a, b, acc, false);
 }
 
-// The eight codes of one packed word as four half2 of exact small integers minus the zero point:
-//   d[0] = (q0 - z, q4 - z), d[1] = (q1 - z, q5 - z), d[2] = (q2 - z, q6 - z), d[3] = (q3 - z, q7 - z).
-// 0x6400 is 1024.0 (ulp 1): OR-ing a nibble into bits 0..3 gives 1024 + q exactly.
+// Bit patterns used to turn 4-bit codes into fp16 values without any integer-to-float conversion:
+// 0x6400 is 1024.0 (ulp 1): OR-ing a nibble into bits 0..3 gives 1024 + q exactly;
 // 0x5400 is 64.0 (ulp 1/16): OR-ing a nibble into bits 4..7 gives 64 + q exactly.
-// neg_lo = (-(1024 + z)) x2 and neg_hi = (-(64 + z)) x2; both sums are exact in fp16.
-__device__ __forceinline__ void codes_minus_zero(uint32_t w, half2_t neg_lo, half2_t neg_hi, half2_t d[4])
+// The constants are kept in registers (not literals) so that each pair costs ONE v_and_or_b32.
+struct NibbleMagic {
+    uint32_t mask_lo, mask_hi, bias_lo, bias_hi;
+    __device__ __forceinline__ NibbleMagic()
+    {
+        mask_lo = 0x000f000fu;
+        mask_hi = 0x00f000f0u;
+        bias_lo = 0x64006400u;
+        bias_hi = 0x54005400u;
+        asm volatile("" : "+s"(mask_lo), "+s"(mask_hi), "+v"(bias_lo), "+v"(bias_hi));
+    }
+};
+
+// The eight codes of one packed word as four half2 that still carry their bias:
+//   b[0] = (1024 + q0, 1024 + q4), b[1] = (64 + q1, 64 + q5), b[2] = (1024 + q2, 1024 + q6), b[3] = (64 + q3, 64 + q7).
+__device__ __forceinline__ void biased_codes(uint32_t w, const NibbleMagic &k, half2_t b[4])
 {
     const uint32_t w8 = w >> 8;
-    d[0] = as_half2((w & 0x000f000fu) | 0x64006400u) + neg_lo;
-    d[1] = as_half2((w & 0x00f000f0u) | 0x54005400u) + neg_hi;
-    d[2] = as_half2((w8 & 0x000f000fu) | 0x64006400u) + neg_lo;
-    d[3] = as_half2((w8 & 0x00f000f0u) | 0x54005400u) + neg_hi;
+    b[0] = as_half2((w & k.mask_lo) | k.bias_lo);
+    b[1] = as_half2((w & k.mask_hi) | k.bias_hi);
+    b[2] = as_half2((w8 & k.mask_lo) | k.bias_lo);
+    b[3] = as_half2((w8 & k.mask_hi) | k.bias_hi);
+}
+
+// Same, with the bias and the zero point taken off: exact small integers q - z.
+// neg_lo = (-(1024 + z)) x2 and neg_hi = (-(64 + z)) x2; both sums are exact in fp16.
+__device__ __forceinline__ void codes_minus_zero(uint32_t w, const NibbleMagic &k, half2_t neg_lo, half2_t neg_hi,
+                                                 half2_t d[4])
+{
+    biased_codes(w, k, d);
+    d[0] += neg_lo;
+    d[1] += neg_hi;
+    d[2] += neg_lo;
+    d[3] += neg_hi;
+}
+
+// Global loads of one step of one lane: UNROLL chunks of R packed rows, plus their scale / zero words.
+template <int R, int UNROLL>
+struct StepRegs {
+    uint4 wq[UNROLL][R];
+    half4_t sc[UNROLL];
+    uint32_t zb[UNROLL];
+};
+
+// Scratch traffic between workgroups goes through device-scope (sc1) accesses that are coherent
+// across the XCDs' L2 caches by themselves, so no cache write-back / invalidate fence is needed.
+__device__ __forceinline__ void store_device_scope(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_device_scope(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int MB, int LPR, int R, bool ACT>
@@ -83,9 +130,17 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
     constexpr int RW = kWaves * RL;       // row lanes per workgroup
     constexpr int CT = LPR * 4;           // columns per workgroup
     constexpr int MC = MB < 4 ? MB : 4;   // batch rows per cross-wavefront reduction round
-    constexpr bool SCALE_W = ACT || MB >= 8;  // scale the weights (true) or the per-chunk sums (false)
+    // Two ways to apply zero point and scale.  FACTORED (small batches, memory bound): contract the
+    // biased codes directly, sum_k x_k (bias_k + q_k), and correct once per chunk with sums of x
+    // that were prepared while staging:  sum_k x_k (q_k - z) = D - sum_k bias_k x_k - z sum_k x_k,
+    // then scale the chunk sum.  Otherwise (act-order or large batches): form the fp16 weight
+    // s * (q - z) per element and contract it.
+    constexpr bool FACTORED = !ACT && MB < 8;
+    constexpr int UNROLL = ACT ? 1 : 2;   // chunks in flight per lane and step (act-order needs the registers)
+    constexpr int STEP = RW * UNROLL;     // chunks a workgroup consumes per step
 
     extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ int s_last;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -96,11 +151,11 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
     const int tile = blockIdx.x % a.tiles_n;
     const int slice = blockIdx.x / a.tiles_n;
     const int n0 = tile * CT + cq * 4;
-    const bool col_ok = n0 < a.N;
     const int N = a.N;
 
     const int c0 = slice * a.chunks_per_slice;
     const int c1 = min(c0 + a.chunks_per_slice, a.total_chunks);
+    const int nchunks = c1 - c0;
     const int kbeg = c0 * R * 8;
     const int kend = min(c1 * R * 8, a.K);
     const int Ls = kend - kbeg;  // activations of this slice, per batch row (multiple of 8)
@@ -108,22 +163,62 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
     // ---- LDS carve-up ----
     half_t *xs = reinterpret_cast<half_t *>(smem);                      // [MB][Ls], pair-permuted
     size_t off = ((size_t)MB * Ls * sizeof(half_t) + 15) & ~(size_t)15;
+    float2 *xc = reinterpret_cast<float2 *>(smem + off);                // FACTORED: [MB][nchunks] (sum bias*x, sum x)
+    off += FACTORED ? (((size_t)MB * nchunks * sizeof(float2) + 15) & ~(size_t)15) : 0;
     float *red = reinterpret_cast<float *>(smem + off);                 // [kWaves][MC][CT]
     off += (size_t)kWaves * MC * CT * sizeof(float);
     int *gl = reinterpret_cast<int *>(smem + off);                      // ACT: [Ls] group of each k
     uint32_t *tab = reinterpret_cast<uint32_t *>(smem + off + (ACT ? (size_t)Ls * sizeof(int) : 0));  // ACT: [groups][CT]
 
-    // ---- stage the activations of this slice (128-bit loads), in the order (0,4,1,5,2,6,3,7) ----
+    // Every load below is made unconditional by clamping its chunk / row to the last valid one of the
+    // slice; what a clamped (out-of-range) chunk contributes is zeroed when it is used.
+    using Regs = StepRegs<R, UNROLL>;
+    auto issue = [&](int u0, Regs &r) {
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j) {
+            const int u = min(u0 + j * RW, c1 - 1);
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr) {
+                const int row = min(u * R + rr, a.rows - 1);
+                r.wq[j][rr] = *reinterpret_cast<const uint4 *>(a.qweight + (size_t)row * N + n0);
+            }
+            if (!ACT) {
+                const int grp = a.chunk_group_shift >= 0 ? (u >> a.chunk_group_shift) : (u * R) / a.rows_per_group;
+                r.sc[j] = *reinterpret_cast<const half4_t *>(a.scales + (size_t)grp * N + n0);
+                r.zb[j] = a.qzeros[(size_t)grp * (N >> 3) + (n0 >> 3)] >> ((n0 & 4) * 4);
+            }
+        }
+    };
+
+    const bool active = n0 < N && c0 + rid < c1;  // this lane owns real columns and at least one chunk
+    Regs ra, rb;
+    if (active)
+        issue(c0 + rid, ra);  // weights are in flight while the activations are staged
+
+    // ---- stage the activations of this slice (128-bit loads), one chunk of R packed rows per thread and
+    //      turn, each group of eight stored in the order (0,4,1,5,2,6,3,7) that the dequantised pairs need ----
     {
-        const int vecs = Ls >> 3;
-        for (int i = tid; i < MB * vecs; i += kThreads) {
-            const int m = i / vecs;
-            const int v = i - m * vecs;
-            half8_t h = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (m < a.M)
-                h = *reinterpret_cast<const half8_t *>(a.x + (size_t)m * a.K + kbeg + v * 8);
-            half8_t p = {h[0], h[4], h[1], h[5], h[2], h[6], h[3], h[7]};
-            *reinterpret_cast<half8_t *>(xs + (size_t)m * Ls + v * 8) = p;
+        for (int i = tid; i < MB * nchunks; i += kThreads) {
+            const int m = MB == 1 ? 0 : i / nchunks;
+            const int ch = i - m * nchunks;
+            float s_lo = 0.f, s_hi = 0.f;  // sums of x over the k that get bias 1024 / bias 64
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr) {
+                const int kk = (ch * R + rr) * 8;  // offset inside the slice
+                if (kk < Ls) {
+                    half8_t h = {0, 0, 0, 0, 0, 0, 0, 0};
+                    if (m < a.M)
+                        h = *reinterpret_cast<const half8_t *>(a.x + (size_t)m * a.K + kbeg + kk);
+                    half8_t p = {h[0], h[4], h[1], h[5], h[2], h[6], h[3], h[7]};
+                    *reinterpret_cast<half8_t *>(xs + (size_t)m * Ls + kk) = p;
+                    if (FACTORED) {
+                        s_lo += ((float)h[0] + (float)h[4]) + ((float)h[2] + (float)h[6]);
+                        s_hi += ((float)h[1] + (float)h[5]) + ((float)h[3] + (float)h[7]);
+                    }
+                }
+            }
+            if (FACTORED)
+                xc[(size_t)m * nchunks + ch] = make_float2(1024.f * s_lo + 64.f * s_hi, s_lo + s_hi);
         }
         if (ACT) {
             for (int i = tid; i < Ls; i += kThreads)
@@ -151,118 +246,131 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
         for (int c = 0; c < 4; ++c)
             acc[m][c] = 0.f;
 
-    constexpr int UNROLL = 2;  // chunks in flight per lane
-    if (col_ok) {
-        for (int u0 = c0 + rid; u0 < c1; u0 += RW * UNROLL) {
-            uint4 wq[UNROLL][R];
-            half4_t sc[UNROLL];
-            uint32_t zb[UNROLL];
-            // ---- issue every global load of this step first ----
+    const NibbleMagic magic;
+
+    // dequantise and contract the chunks held in `r`
+    auto consume = [&](int u0, const Regs &r) {
 #pragma unroll
-            for (int j = 0; j < UNROLL; ++j) {
-                const int u = u0 + j * RW;
+        for (int j = 0; j < UNROLL; ++j) {
+            const bool valid = u0 + j * RW < c1;
+            const int u = min(u0 + j * RW, c1 - 1);
+            half2_t neg_lo[4], neg_hi[4], s2[4];
+            float sf[4], zf[4];
+            float gacc[MB][4];
+            if (!ACT) {
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const int row = u * R + r;
-                    wq[j][r] = make_uint4(0, 0, 0, 0);
-                    if (u < c1 && row < a.rows)
-                        wq[j][r] = *reinterpret_cast<const uint4 *>(a.qweight + (size_t)row * N + n0);
-                }
-                sc[j] = half4_t{0, 0, 0, 0};
-                zb[j] = 0;
-                if (!ACT && u < c1) {
-                    const int grp = (u * R) / a.rows_per_group;
-                    sc[j] = *reinterpret_cast<const half4_t *>(a.scales + (size_t)grp * N + n0);
-                    zb[j] = a.qzeros[(size_t)grp * (N >> 3) + (n0 >> 3)] >> ((n0 & 4) * 4);
-                }
-            }
-            // ---- dequantise and contract ----
-#pragma unroll
-            for (int j = 0; j < UNROLL; ++j) {
-                const int u = u0 + j * RW;
-                if (u >= c1)
-                    break;
-                half2_t neg_lo[4], neg_hi[4], s2[4];
-                float gacc[MB][4];
-                if (!ACT) {
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        const uint32_t z = (zb[j] >> (4 * c)) & 15u;
+                for (int c = 0; c < 4; ++c) {
+                    const uint32_t z = (r.zb[j] >> (4 * c)) & 15u;
+                    const half_t s = valid ? r.sc[j][c] : (half_t)0;  // a clamped chunk contributes nothing
+                    if (FACTORED) {
+                        zf[c] = (float)z;
+                        sf[c] = (float)s;
+                    } else {
                         neg_lo[c] = as_half2(0xE400E400u | (z * 0x00010001u));
                         neg_hi[c] = as_half2(0xD400D400u | (z * 0x00100010u));
-                        s2[c] = half2_t{sc[j][c], sc[j][c]};
+                        s2[c] = half2_t{s, s};
                     }
+                }
+                if (FACTORED) {
 #pragma unroll
                     for (int m = 0; m < MB; ++m)
 #pragma unroll
                         for (int c = 0; c < 4; ++c)
                             gacc[m][c] = 0.f;
                 }
+            }
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const int row = u * R + r;
-                    if (row >= a.rows)
-                        break;
-                    const int koff = row * 8 - kbeg;
-                    const uint32_t w[4] = {wq[j][r].x, wq[j][r].y, wq[j][r].z, wq[j][r].w};
-                    half2_t d[4][4];
-                    if (!ACT) {
+            for (int rr = 0; rr < R; ++rr) {
+                const bool row_valid = valid && (u * R + rr < a.rows);
+                const int row = min(u * R + rr, a.rows - 1);
+                const int koff = row * 8 - kbeg;
+                const uint32_t w[4] = {r.wq[j][rr].x, r.wq[j][rr].y, r.wq[j][rr].z, r.wq[j][rr].w};
+                half2_t d[4][4];
+                if (FACTORED) {
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) {
-                            codes_minus_zero(w[c], neg_lo[c], neg_hi[c], d[c]);
-                            if (SCALE_W) {
+                    for (int c = 0; c < 4; ++c)
+                        biased_codes(w[c], magic, d[c]);
+                } else if (!ACT) {
 #pragma unroll
-                                for (int i = 0; i < 4; ++i)
-                                    d[c][i] = d[c][i] * s2[c];
-                            }
-                        }
-                    } else {
-                        // every k of the packed row may belong to a different group
-                        const int4 ga = *reinterpret_cast<const int4 *>(gl + koff);
-                        const int4 gb = *reinterpret_cast<const int4 *>(gl + koff + 4);
-                        const int g[8] = {ga.x, ga.y, ga.z, ga.w, gb.x, gb.y, gb.z, gb.w};
-                        uint4 t[8];
+                    for (int c = 0; c < 4; ++c) {
+                        codes_minus_zero(w[c], magic, neg_lo[c], neg_hi[c], d[c]);
 #pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            t[e] = *reinterpret_cast<const uint4 *>(tab + (size_t)g[e] * CT + cq * 4);
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const uint32_t ta[4] = {t[i].x, t[i].y, t[i].z, t[i].w};          // k = 8*row + i
-                            const uint32_t tb[4] = {t[i + 4].x, t[i + 4].y, t[i + 4].z, t[i + 4].w};  // k + 4
-#pragma unroll
-                            for (int c = 0; c < 4; ++c) {
-                                const uint32_t h = ((w[c] >> (4 * i)) & 0x000f000fu) | 0x64006400u;
-                                const uint32_t nz = (ta[c] >> 16) | (tb[c] & 0xffff0000u);
-                                const uint32_t ss = (ta[c] & 0xffffu) | (tb[c] << 16);
-                                d[c][i] = (as_half2(h) + as_half2(nz)) * as_half2(ss);
-                            }
-                        }
+                        for (int i = 0; i < 4; ++i)
+                            d[c][i] = d[c][i] * s2[c];
                     }
+                } else {
+                    // every k of the packed row may belong to a different group
+                    const int4 ga = *reinterpret_cast<const int4 *>(gl + koff);
+                    const int4 gb = *reinterpret_cast<const int4 *>(gl + koff + 4);
+                    const int g[8] = {ga.x, ga.y, ga.z, ga.w, gb.x, gb.y, gb.z, gb.w};
+                    uint4 t[8];
 #pragma unroll
-                    for (int m = 0; m < MB; ++m) {
-                        const uint4 xv = *reinterpret_cast<const uint4 *>(xs + (size_t)m * Ls + koff);
-                        const half2_t xp[4] = {as_half2(xv.x), as_half2(xv.y), as_half2(xv.z), as_half2(xv.w)};
+                    for (int e = 0; e < 8; ++e)
+                        t[e] = *reinterpret_cast<const uint4 *>(tab + (size_t)g[e] * CT + cq * 4);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t ta[4] = {t[i].x, t[i].y, t[i].z, t[i].w};                  // k = 8*row + i
+                        const uint32_t tb[4] = {t[i + 4].x, t[i + 4].y, t[i + 4].z, t[i + 4].w};  // k + 4
 #pragma unroll
                         for (int c = 0; c < 4; ++c) {
-                            float s = SCALE_W ? acc[m][c] : gacc[m][c];
-#pragma unroll
-                            for (int i = 0; i < 4; ++i)
-                                s = dot2(d[c][i], xp[i], s);
-                            if (SCALE_W)
-                                acc[m][c] = s;
-                            else
-                                gacc[m][c] = s;
+                            const uint32_t h = ((w[c] >> (4 * i)) & magic.mask_lo) | magic.bias_lo;
+                            const uint32_t nz = (ta[c] >> 16) | (tb[c] & 0xffff0000u);
+                            const uint32_t ss = (ta[c] & 0xffffu) | (tb[c] << 16);
+                            d[c][i] = (as_half2(h) + as_half2(nz)) * as_half2(ss);
                         }
                     }
                 }
-                if (!SCALE_W) {
 #pragma unroll
-                    for (int m = 0; m < MB; ++m)
+                for (int m = 0; m < MB; ++m) {
+                    uint4 xv = *reinterpret_cast<const uint4 *>(xs + (size_t)m * Ls + koff);
+                    if (ACT && !row_valid)
+                        xv = make_uint4(0, 0, 0, 0);
+                    const half2_t xp[4] = {as_half2(xv.x), as_half2(xv.y), as_half2(xv.z), as_half2(xv.w)};
 #pragma unroll
-                        for (int c = 0; c < 4; ++c)
-                            acc[m][c] = __builtin_fmaf((float)sc[j][c], gacc[m][c], acc[m][c]);
+                    for (int c = 0; c < 4; ++c) {
+                        float s = FACTORED ? gacc[m][c] : acc[m][c];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            s = dot2(d[c][i], xp[i], s);
+                        if (FACTORED)
+                            gacc[m][c] = s;
+                        else
+                            acc[m][c] = s;
+                    }
                 }
             }
+            if (FACTORED) {
+#pragma unroll
+                for (int m = 0; m < MB; ++m) {
+                    const float2 bs = xc[(size_t)m * nchunks + (u - c0)];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float t = __builtin_fmaf(-zf[c], bs.y, gacc[m][c] - bs.x);  // sum_k x_k (q_k - z)
+                        acc[m][c] = __builtin_fmaf(sf[c], t, acc[m][c]);
+                    }
+                }
+            }
+        }
+    };
+
+    if (active) {
+        // software pipeline over two register sets: the next step's weights fly while this step is consumed
+        int u0 = c0 + rid;
+        while (true) {
+            bool more = u0 + STEP < c1;
+            if (more)
+                issue(u0 + STEP, rb);
+            consume(u0, ra);
+            if (!more)
+                break;
+            u0 += STEP;
+            more = u0 + STEP < c1;
+            if (more)
+                issue(u0 + STEP, ra);
+            consume(u0, rb);
+            if (!more)
+                break;
+            u0 += STEP;
         }
     }
 
@@ -302,35 +410,46 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
                 if (a.split_k == 1)
                     a.out[(size_t)m * N + n] = (half_t)s;
                 else
-                    a.partial[((size_t)slice * a.M + m) * N + n] = s;
+                    store_device_scope(a.partial + ((size_t)slice * a.M + m) * N + n, s);
             }
         }
     }
 
     // ---- combine the K slices: the last workgroup of this column tile adds them in slice order ----
     if (a.split_k > 1) {
-        __shared__ int s_last;
-        __threadfence();  // release this workgroup's partials device-wide
+        // all partial stores of this workgroup have been acknowledged before its arrival is counted
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         if (tid == 0) {
-            const unsigned prev = atomicAdd(a.counters + tile, 1u);
+            const unsigned prev =
+                __hip_atomic_fetch_add(a.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             s_last = (prev == (unsigned)(a.split_k - 1));
         }
         __syncthreads();
         if (s_last) {
-            __threadfence();  // acquire the other workgroups' partials
             for (int i = tid; i < a.M * CT; i += kThreads) {
                 const int m = i / CT;
                 const int n = tile * CT + (i - m * CT);
                 if (n < N) {
+                    // eight loads in flight at a time; the additions stay in slice order
                     float s = 0.f;
-                    for (int sl = 0; sl < a.split_k; ++sl)
-                        s += a.partial[((size_t)sl * a.M + m) * N + n];
+                    for (int sl0 = 0; sl0 < a.split_k; sl0 += 8) {
+                        float v[8];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const int sl = min(sl0 + j, a.split_k - 1);
+                            v[j] = load_device_scope(a.partial + ((size_t)sl * a.M + m) * N + n);
+                        }
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            s += (sl0 + j < a.split_k) ? v[j] : 0.f;
+                    }
                     a.out[(size_t)m * N + n] = (half_t)s;
                 }
             }
             if (tid == 0)
-                atomicExch(a.counters + tile, 0u);  // ready for the next launch
+                __hip_atomic_store(a.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
         }
     }
 }

@@ -39,6 +39,8 @@ hipError_t launch_mb<GPTQ_DECODE_MB>(const Args &a, int lpr, int chunk_rows, boo
     }
     if (chunk_rows == 4) {
         switch (lpr) {
+        case 4: return launch_one<MB, 4, 4, false>(a, lds_bytes, stream);
+        case 8: return launch_one<MB, 8, 4, false>(a, lds_bytes, stream);
         case 16: return launch_one<MB, 16, 4, false>(a, lds_bytes, stream);
         case 32: return launch_one<MB, 32, 4, false>(a, lds_bytes, stream);
         case 64: return launch_one<MB, 64, 4, false>(a, lds_bytes, stream);

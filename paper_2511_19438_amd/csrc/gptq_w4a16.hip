@@ -214,8 +214,8 @@ int gptq_w4a16_set_workspace(void *dev_ptr, size_t bytes)
         return GPTQ_HIP_ERROR;
     if (dev_ptr && (reinterpret_cast<uintptr_t>(dev_ptr) & 255u) != 0)
         return GPTQ_MISALIGNED;
-    if (dev_ptr && bytes < 4096)
-        return GPTQ_WORKSPACE_TOO_SMALL;
+    if (dev_ptr && bytes < decode_counter_bytes(0))
+        return GPTQ_WORKSPACE_TOO_SMALL;  // not even room for the arrival counters
     std::lock_guard<std::mutex> lock(g_mutex);
     Workspace &ws = g_ws[dev];
     if (ws.ptr && ws.owned) {

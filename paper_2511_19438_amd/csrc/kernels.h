@@ -32,7 +32,7 @@ hipError_t launch_dequant(const uint32_t *qweight, const uint32_t *qzeros, const
 
 // ---- decode: split-K vector kernel, M <= 16 per launch ----
 struct DecodePlan {
-    int cols_per_wg;   // 64, 128 or 256
+    int cols_per_wg;   // 16, 32, 64, 128 or 256
     int split_k;       // number of K slices
     int chunk_rows;    // packed rows handled per lane per step (1, 2 or 4), divides group_size/8
     int chunks_per_slice;

@@ -12,24 +12,32 @@ template <> hipError_t launch_tile<3>(const Args &, int, hipStream_t);
 template <> hipError_t launch_tile<4>(const Args &, int, hipStream_t);
 template <> hipError_t launch_tile<5>(const Args &, int, hipStream_t);
 template <> hipError_t launch_tile<6>(const Args &, int, hipStream_t);
+template <> hipError_t launch_tile<7>(const Args &, int, hipStream_t);
+template <> hipError_t launch_tile<8>(const Args &, int, hipStream_t);
+template <> hipError_t launch_tile<9>(const Args &, int, hipStream_t);
+template <> hipError_t launch_tile<10>(const Args &, int, hipStream_t);
 }  // namespace prefill
 
 namespace {
 
 struct TileShape {
     int bm, bn;
-    double rate;  // relative MFMA efficiency of the tile (bigger tiles amortise operand traffic better)
+    double rate;  // measured in-loop MFMA rate relative to the 256x256 tile with 2x2 wavefronts (0 = not auto-selected)
 };
-constexpr TileShape kTiles[7] = {{0, 0, 0.0},      {256, 256, 1.00}, {256, 128, 0.92}, {128, 128, 0.80},
-                                 {128, 256, 0.88}, {64, 128, 0.55},  {32, 256, 0.40}};
-constexpr int kNumTiles = 6;
+// ids 1..10, see the plan documentation in the public header
+constexpr TileShape kTiles[11] = {{0, 0, 0.0},      {256, 256, 0.0},  {256, 128, 0.0},  {128, 128, 0.68},
+                                  {128, 256, 0.0},  {64, 128, 0.45},  {32, 256, 0.30},  {256, 256, 0.0},
+                                  {128, 256, 0.84}, {256, 256, 1.00}, {256, 256, 0.0}};
+constexpr int kNumTiles = 10;
 constexpr int kComputeUnits = 256;
 
 int mode_of(const Problem &p)
 {
     if (p.g_idx)
         return prefill::kActOrder;
-    return (p.group_size % prefill::BK == 0) ? prefill::kGroupPerStage : prefill::kGroupPerRow;
+    // the pipelined kernel moves 16-byte chunks of every operand row: rows of packed zero points (N/8 words)
+    // are 16-byte aligned only when N is a multiple of 32
+    return (p.group_size % 64 == 0 && p.N % 32 == 0) ? prefill::kGroupPerStage : prefill::kGroupPerRow;
 }
 
 }  // namespace
@@ -53,6 +61,8 @@ void prefill_make_plan(const Problem &p, PrefillPlan &plan)
     int best_tile = 3;
     for (int t = 1; t <= kNumTiles; ++t) {
         const TileShape &ts = kTiles[t];
+        if (ts.rate <= 0.0)
+            continue;
         const long long tiles = (long long)((p.M + ts.bm - 1) / ts.bm) * ((p.N + ts.bn - 1) / ts.bn);
         const long long rounds = (tiles + kComputeUnits - 1) / kComputeUnits;
         const double cost = (double)rounds * ts.bm * ts.bn / ts.rate;
@@ -86,6 +96,10 @@ hipError_t launch_prefill(const Problem &p, const PrefillPlan &plan, hipStream_t
     case 4: return prefill::launch_tile<4>(a, mode, stream);
     case 5: return prefill::launch_tile<5>(a, mode, stream);
     case 6: return prefill::launch_tile<6>(a, mode, stream);
+    case 7: return prefill::launch_tile<7>(a, mode, stream);
+    case 8: return prefill::launch_tile<8>(a, mode, stream);
+    case 9: return prefill::launch_tile<9>(a, mode, stream);
+    case 10: return prefill::launch_tile<10>(a, mode, stream);
     default: return hipErrorInvalidValue;
     }
 }

@@ -1,9 +1,9 @@
-// Instantiates the MFMA kernel for ONE tile configuration (GPTQ_PREFILL_TILE, set on the compiler
+// Instantiates the MFMA kernels for ONE tile configuration (GPTQ_PREFILL_TILE, set on the compiler
 // command line) so that the configurations compile in parallel.
 #include "prefill_kernel.h"
 
 #ifndef GPTQ_PREFILL_TILE
-#error "compile with -DGPTQ_PREFILL_TILE=<1..6>"
+#error "compile with -DGPTQ_PREFILL_TILE=<1..10>"
 #endif
 
 namespace gptq {
@@ -14,31 +14,38 @@ hipError_t launch_tile(const Args &a, int mode, hipStream_t stream);
 
 namespace {
 
+// rows x columns per workgroup, wavefront grid, k per stage, stage buffers in the LDS ring
 #if GPTQ_PREFILL_TILE == 1
-constexpr int BM = 256, BN = 256, WM = 1, WN = 4;
+constexpr int BM = 256, BN = 256, WM = 1, WN = 4, BK = 64, NBUF = 3;
 #elif GPTQ_PREFILL_TILE == 2
-constexpr int BM = 256, BN = 128, WM = 2, WN = 2;
+constexpr int BM = 256, BN = 128, WM = 2, WN = 2, BK = 64, NBUF = 4;
 #elif GPTQ_PREFILL_TILE == 3
-constexpr int BM = 128, BN = 128, WM = 2, WN = 2;
+constexpr int BM = 128, BN = 128, WM = 2, WN = 2, BK = 64, NBUF = 3;
 #elif GPTQ_PREFILL_TILE == 4
-constexpr int BM = 128, BN = 256, WM = 1, WN = 4;
+constexpr int BM = 128, BN = 256, WM = 1, WN = 4, BK = 64, NBUF = 6;
 #elif GPTQ_PREFILL_TILE == 5
-constexpr int BM = 64, BN = 128, WM = 1, WN = 4;
+constexpr int BM = 64, BN = 128, WM = 1, WN = 4, BK = 64, NBUF = 4;
 #elif GPTQ_PREFILL_TILE == 6
-constexpr int BM = 32, BN = 256, WM = 1, WN = 4;
+constexpr int BM = 32, BN = 256, WM = 1, WN = 4, BK = 64, NBUF = 4;
+#elif GPTQ_PREFILL_TILE == 7
+constexpr int BM = 256, BN = 256, WM = 1, WN = 4, BK = 32, NBUF = 7;
+#elif GPTQ_PREFILL_TILE == 8
+constexpr int BM = 128, BN = 256, WM = 1, WN = 4, BK = 64, NBUF = 3;
+#elif GPTQ_PREFILL_TILE == 9
+constexpr int BM = 256, BN = 256, WM = 2, WN = 2, BK = 64, NBUF = 3;
+#elif GPTQ_PREFILL_TILE == 10
+constexpr int BM = 256, BN = 256, WM = 2, WN = 2, BK = 32, NBUF = 6;
 #else
 #error "unknown tile id"
 #endif
 
-template <int MODE>
-hipError_t launch_mode(Args a, hipStream_t stream)
+template <typename Kernel>
+hipError_t launch(Kernel kernel, Args a, size_t lds, hipStream_t stream)
 {
     a.tiles_m = (a.M + BM - 1) / BM;
     a.tiles_n = (a.N + BN - 1) / BN;
     const int total = a.tiles_m * a.tiles_n;
     const unsigned grid = 8u * (unsigned)((total + 7) / 8);
-    const size_t lds = 2 * (size_t)BM * BK * sizeof(half_t);
-    auto kernel = prefill_kernel<BM, BN, WM, WN, MODE>;
     if (lds > 48 * 1024) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -55,12 +62,14 @@ template <>
 hipError_t launch_tile<GPTQ_PREFILL_TILE>(const Args &a, int mode, hipStream_t stream)
 {
     if (mode == kGroupPerStage)
-        return launch_mode<kGroupPerStage>(a, stream);
+        return launch(prefill_pipelined_kernel<BM, BN, WM, WN, BK, NBUF>, a,
+                      (size_t)NBUF * StageLayout<BM, BN, BK>::BYTES, stream);
 #if GPTQ_PREFILL_TILE == 3
+    const size_t lds = 2 * (size_t)BM * 64 * sizeof(half_t);
     if (mode == kGroupPerRow)
-        return launch_mode<kGroupPerRow>(a, stream);
+        return launch(prefill_general_kernel<BM, BN, WM, WN, kGroupPerRow>, a, lds, stream);
     if (mode == kActOrder)
-        return launch_mode<kActOrder>(a, stream);
+        return launch(prefill_general_kernel<BM, BN, WM, WN, kActOrder>, a, lds, stream);
 #endif
     return hipErrorInvalidValue;
 }
