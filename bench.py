@@ -48,6 +48,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill (MFMA) leg")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-context", action="store_true", help="skip the device-copy / dense-matmul context lines")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device copy (reference kernel for the HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -139,8 +142,15 @@ def main():
     achieved = bytes_per_launch / avg_launch_s / 1e9
     roofline = {"bound": "hbm", "kernel": "decode_kernel<MB=1> (split-K vector kernel)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic("decode_m1_llama7b"),
                 "bytes_per_launch": int(bytes_per_launch), "avg_launch_us": round(avg_launch_s * 1e6, 3)}
+    if args.calibrate_copy:
+        # a plain copy of known size in the same process: the scale for the FETCH_SIZE / WRITE_SIZE counters
+        src = torch.empty(256 * 1024 * 1024, dtype=torch.int32, device="cuda").random_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- prefill half of the metric: M = 2048 on the 7B shapes ----
     prefill = None
@@ -179,7 +189,50 @@ def main():
     if prefill:
         line["prefill"] = prefill["summary"]
         line["roofline_prefill"] = prefill["roofline"]
+    if not args.no_context:
+        line["context"] = context_lines(torch)
     print(json.dumps(line))
+
+
+def measured_traffic(key):
+    """HBM bytes per launch measured with rocprofv3 counters (profiles/traffic.json), or None if not recorded."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(key, {}).get("hbm_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def context_lines(torch, reps=10):
+    """What the box itself achieves: a device copy and a dense fp16 matmul, as context for the roofline fractions."""
+    n = 256 * 1024 * 1024
+    src = torch.empty(n, dtype=torch.int32, device="cuda").random_()
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2.0 * n * 4 * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+    M, K, N = 2048, 4096, 22016
+    x = torch.randn((M, K), device="cuda").half()
+    w = torch.randn((K, N), device="cuda").half()
+    for _ in range(3):
+        torch.matmul(x, w)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        torch.matmul(x, w)
+    e1.record()
+    torch.cuda.synchronize()
+    dense = 2.0 * M * K * N * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return {"device_copy_GBps_read_plus_write": round(copy_gbs, 1),
+            "torch_matmul_fp16_dense_TFLOPs_M2048_K4096_N22016": round(dense, 1)}
 
 
 def prefill_leg(torch, B, workloads, layers, M=2048, reps=15, warm=3):
@@ -213,7 +266,8 @@ def prefill_leg(torch, B, workloads, layers, M=2048, reps=15, warm=3):
         "summary": {"value": round(agg, 1), "unit": "TFLOP/s", "M": M, "shapes": results},
         "roofline": {"bound": "mfma", "kernel": f"prefill_kernel (fp16 MFMA), {dominant['shape']}",
                      "achieved": dominant["tflops"], "peak": MFMA_FP16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(dominant["tflops"] / MFMA_FP16_PEAK_TFLOPS, 4), "traffic": None},
+                     "frac": round(dominant["tflops"] / MFMA_FP16_PEAK_TFLOPS, 4),
+                     "traffic": measured_traffic("prefill_m2048_k4096_n22016")},
     }
 
 
