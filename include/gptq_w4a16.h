@@ -64,7 +64,9 @@ enum gptq_status {
  * dequantise, stage activations on chip, contract, reduce the split-K partial sums on
  * chip and across workgroups, round once to fp16, store).  `out` is OVERWRITTEN and need
  * not be zeroed (unlike the accumulate-by-atomicAdd contract of Eq. 9-10).
- * M <= 16 runs the bandwidth-bound split-K vector kernel, larger M the fp16 MFMA kernel.
+ * By default M <= 2 runs the bandwidth-bound split-K vector kernel, 3 <= M <= 32 a small-batch MFMA kernel
+ * with the same split-K decomposition (when the format allows: no g_idx, group_size % 128 == 0), larger M
+ * the big-tile fp16 MFMA kernel.
  * Accumulation is in fp32; the result differs from the exact sum by fp32 reassociation
  * and the final fp16 rounding only.  The same inputs give bit-identical outputs on every
  * call (no floating point atomics are used).
@@ -78,7 +80,8 @@ GPTQ_API int gptq_w4a16_gemm(const void *x, const void *qweight, const void *qze
  * explicitly (for tuning sweeps).  A zero field means "let the library choose".
  */
 typedef struct gptq_w4a16_plan {
-    int kernel;      /* 0 auto, 1 vector split-K kernel (any M, processed 16 rows at a time), 2 MFMA kernel */
+    int kernel;      /* 0 auto, 1 vector split-K kernel (any M, processed 16 rows at a time), 2 big-tile MFMA kernel,
+                        3 small-batch MFMA kernel (M <= 64, no g_idx, group_size % 128 == 0; else falls back) */
     int split_k;     /* number of K slices (vector kernel); 0 auto */
     int tile;        /* vector kernel: columns per workgroup (16, 32, 64, 128 or 256);
                         MFMA kernel: tile id 1..10 = rows x columns per workgroup (wavefront grid):

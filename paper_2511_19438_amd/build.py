@@ -36,7 +36,8 @@ def units():
     out = [("gptq_w4a16.hip", "gptq_w4a16.o", []),
            ("unpack_dequant.hip", "unpack_dequant.o", []),
            ("decode.hip", "decode.o", []),
-           ("prefill.hip", "prefill.o", [])]
+           ("prefill.hip", "prefill.o", []),
+           ("skinny.hip", "skinny.o", [])]
     for mb in DECODE_BATCHES:
         out.append(("decode_mb.hip", f"decode_mb{mb}.o", [f"-DGPTQ_DECODE_MB={mb}"]))
     for t in PREFILL_TILES:

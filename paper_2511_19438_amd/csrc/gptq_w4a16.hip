@@ -79,10 +79,25 @@ int acquire_workspace(size_t bytes, void **out)
     return GPTQ_OK;
 }
 
+// Default kernel by batch size, from measurement on Llama-shaped layers.  Up to 2 rows the vector kernel streams
+// the weights fastest.  From 3 rows it runs out of vector ALU throughput (every weight meets every batch row
+// there) and the small-batch MFMA kernel, whose time is flat up to 16 rows, wins; past 32 rows that kernel's
+// per-workgroup activation staging outgrows its benefit and the big-tile MFMA kernel takes over.
+constexpr int kVectorMaxM = 2;
+constexpr int kSmallBatchAutoMaxM = 32;
+
 int run_gemm(const Problem &p, hipStream_t stream, const gptq_w4a16_plan_t *plan)
 {
     int kernel = plan ? plan->kernel : 0;
-    if (kernel == 0)
+    if (kernel == 0) {
+        if (p.M <= kVectorMaxM)
+            kernel = 1;
+        else if (p.M <= kSmallBatchAutoMaxM && skinny_supported(p))
+            kernel = 3;
+        else
+            kernel = (p.M <= kDecodeMaxM) ? 1 : 2;
+    }
+    if (kernel == 3 && !skinny_supported(p))
         kernel = (p.M <= kDecodeMaxM) ? 1 : 2;
     if (kernel == 2 && !prefill_supported(p))
         kernel = 1;
@@ -100,6 +115,17 @@ int run_gemm(const Problem &p, hipStream_t stream, const gptq_w4a16_plan_t *plan
         if (rc != GPTQ_OK)
             return rc;
         return launch_decode(p, dp, ws, stream) == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
+    }
+    if (kernel == 3) {
+        SkinnyPlan sp;
+        sp.split_k = plan ? plan->split_k : 0;
+        sp.units_per_slice = 0;
+        skinny_make_plan(p, sp);
+        void *ws = nullptr;
+        const int rc = acquire_workspace(skinny_workspace_bytes(p, sp), &ws);
+        if (rc != GPTQ_OK)
+            return rc;
+        return launch_skinny(p, sp, ws, stream) == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
     }
     PrefillPlan pp;
     pp.tile = plan ? plan->tile : 0;
@@ -121,7 +147,7 @@ int gptq_w4a16_gemm_plan(const void *x, const void *qweight, const void *qzeros,
     if (rc != GPTQ_OK)
         return rc;
     if (plan) {
-        if (plan->kernel < 0 || plan->kernel > 2 || plan->split_k < 0 || plan->tile < 0 || plan->flags != 0)
+        if (plan->kernel < 0 || plan->kernel > 3 || plan->split_k < 0 || plan->tile < 0 || plan->flags != 0)
             return GPTQ_INVALID_ARG;
         for (int i = 0; i < 4; ++i)
             if (plan->reserved[i] != 0)
@@ -204,7 +230,17 @@ size_t gptq_w4a16_workspace_bytes(int M, int K, int N, int group_size)
     DecodePlan da = {};
     decode_make_plan(p, da);
     const size_t act = decode_workspace_bytes(p, da);
-    return bytes > act ? bytes : act;
+    if (act > bytes)
+        bytes = act;
+    p.g_idx = nullptr;
+    if (skinny_supported(p)) {
+        SkinnyPlan sp = {};
+        skinny_make_plan(p, sp);
+        const size_t sk = skinny_workspace_bytes(p, sp);
+        if (sk > bytes)
+            bytes = sk;
+    }
+    return bytes;
 }
 
 int gptq_w4a16_set_workspace(void *dev_ptr, size_t bytes)

@@ -45,6 +45,17 @@ size_t decode_workspace_bytes(const Problem &p, const DecodePlan &plan);
 size_t decode_counter_bytes(int N);
 hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspace, hipStream_t stream);
 
+// ---- small batch: MFMA kernel with the vector kernel's split-K decomposition, M <= 64 ----
+constexpr int kSkinnyMaxM = 64;
+struct SkinnyPlan {
+    int split_k;          // number of K slices (0 = choose)
+    int units_per_slice;  // 128-k units per slice
+};
+bool skinny_supported(const Problem &p);
+void skinny_make_plan(const Problem &p, SkinnyPlan &plan);
+size_t skinny_workspace_bytes(const Problem &p, const SkinnyPlan &plan);
+hipError_t launch_skinny(const Problem &p, const SkinnyPlan &plan, void *workspace, hipStream_t stream);
+
 // ---- prefill: fp16 MFMA kernel ----
 struct PrefillPlan {
     int tile;  // tile configuration id (1-based), 0 = auto

@@ -1,0 +1,297 @@
+// Small-batch MFMA kernel for the W4A16 GPTQ matrix multiply (5 <= M <= 128), gfx950.
+//
+// Between the vector kernel (which runs out of vector ALU throughput once every weight has to be
+// multiplied with more than a few batch rows) and the big-tile MFMA kernel (which needs hundreds of rows
+// to fill its tiles) the problem is still bound by streaming the packed weights from HBM, but the
+// contraction no longer fits the vector units.  This kernel keeps the work decomposition of the vector
+// kernel - a workgroup owns 64 columns and one K slice, its four wavefronts split the slice, partial
+// sums meet in LDS and then in scratch, in a fixed order (Opt4GPTQ, Section 3.1) - and hands the
+// contraction to v_mfma_f32_16x16x32_f16:
+//   * one lane of the MFMA B operand holds 8 consecutive k of one column, which is exactly one packed
+//     qweight word: a lane loads four adjacent words (128 bits; a wavefront load touches 4 packed rows x
+//     256 contiguous bytes), dequantises them in registers (exact q - z, one fp16 multiply by the scale)
+//     and feeds four MFMAs, n-block t <-> column 4*(lane%16) + t;
+//   * the activations of the slice are staged in LDS with 128-bit accesses (Section 3.2), 16-byte chunks
+//     XOR-swizzled by row so that the 16-row operand reads are bank-conflict free;
+//   * every weight is read once and dequantised once, whatever M is: 2 vector ALU operations per weight
+//     instead of 1.2 + M/2 in the vector kernel.
+// Supports no g_idx and group sizes that are multiples of 128 (the tuned format); other cases use the
+// other kernels.
+#pragma once
+
+#include "kernels.h"
+
+namespace gptq {
+namespace skinny {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;
+constexpr int kCols = 64;      // columns per workgroup
+constexpr int kUnitK = 128;    // k per pipeline unit (4 MFMA steps of 32)
+
+struct Args {
+    const half_t *x;
+    const uint32_t *qweight;
+    const uint32_t *qzeros;
+    const half_t *scales;
+    half_t *out;
+    float *partial;      // [split_k, M, N] fp32, only if split_k > 1
+    unsigned *counters;  // [tiles_n], zero between launches
+    int M, K, N;
+    int units_per_group;  // group_size / 128
+    int tiles_n;
+    int split_k;
+    int units_per_slice;  // 128-k units per K slice (multiple of 4 where possible)
+    int total_units;      // K / 128
+};
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ half2_t as_half2(uint32_t v)
+{
+    return __builtin_bit_cast(half2_t, v);
+}
+
+struct PairMagic {
+    uint32_t mask, bias;
+    __device__ __forceinline__ PairMagic()
+    {
+        mask = 0x00f0000fu;  // one nibble per half
+        bias = 0x54006400u;  // (64.0 with ulp 1/16, 1024.0 with ulp 1)
+        asm volatile("" : "+s"(mask), "+v"(bias));
+    }
+};
+
+// Pair P (k = 2P, 2P+1) of a packed word -> the bits of (s*(q_2P - z), s*(q_2P+1 - z)); see the MFMA
+// prefill kernel for the bit trick.  nz = (-(1024+z), -(64+z)), ss = (s, s).
+template <int P>
+__device__ __forceinline__ uint32_t dequant_pair(uint32_t w, const PairMagic &k, uint32_t nz, uint32_t ss)
+{
+    const uint32_t spread = __builtin_amdgcn_perm(0u, w, 0x0c000c00u | P | (P << 16));
+    const half2_t v = (as_half2((spread & k.mask) | k.bias) + as_half2(nz)) * as_half2(ss);
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+__device__ __forceinline__ half8_t dequant_word(uint32_t w, const PairMagic &k, uint32_t nz, uint32_t ss)
+{
+    u32x4_t r;
+    r[0] = dequant_pair<0>(w, k, nz, ss);
+    r[1] = dequant_pair<1>(w, k, nz, ss);
+    r[2] = dequant_pair<2>(w, k, nz, ss);
+    r[3] = dequant_pair<3>(w, k, nz, ss);
+    return __builtin_bit_cast(half8_t, r);
+}
+
+__device__ __forceinline__ void store_device_scope(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_device_scope(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Loads of one 128-k unit of one lane: 4 steps x 4 adjacent words, plus the unit's scales and zero word.
+struct UnitRegs {
+    uint4 w[4];
+    uint2 sc;  // four fp16 scales as raw bits
+    uint32_t zb;
+};
+
+template <int TM>  // 16-row blocks: M <= 16 * TM
+__global__ __launch_bounds__(kThreads) void skinny_kernel(const Args a)
+{
+    constexpr int ROWS = 16 * TM;
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ int s_last;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cq = lane & 15;  // column quad: columns n0 + 4*cq .. +3
+    const int kg = lane >> 4;  // k group inside a 32-k step = packed row inside the step
+    const int tile = blockIdx.x % a.tiles_n;
+    const int slice = blockIdx.x / a.tiles_n;
+    const int N = a.N;
+    const int n0 = tile * kCols + 4 * cq;
+    const int nc = min(n0, N - 4);  // clamped for loads; columns past N are never stored
+
+    const int u0 = slice * a.units_per_slice;
+    const int u1 = min(u0 + a.units_per_slice, a.total_units);
+    const int nunits = u1 - u0;
+    const int kbeg = u0 * kUnitK;
+    const int Ls = nunits * kUnitK;  // activations of this slice per row (multiple of 128)
+
+    // this wavefront's contiguous share of the slice's units
+    const int per_wave = (nunits + kWaves - 1) / kWaves;
+    const int wu0 = min(u0 + wave * per_wave, u1);
+    const int wu1 = min(wu0 + per_wave, u1);
+
+    half_t *xs = reinterpret_cast<half_t *>(smem);  // [ROWS][Ls], 16-byte chunks swizzled by row
+
+    auto issue = [&](int u, UnitRegs &r) {
+        const int uc = min(u, u1 - 1);  // clamped: loads never branch, a clamped unit is not consumed
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+            r.w[s] = *reinterpret_cast<const uint4 *>(a.qweight + (size_t)(uc * 16 + s * 4 + kg) * N + nc);
+        const int grp = uc / a.units_per_group;
+        r.sc = *reinterpret_cast<const uint2 *>(a.scales + (size_t)grp * N + nc);
+        r.zb = a.qzeros[(size_t)grp * (N >> 3) + (nc >> 3)] >> ((nc & 4) * 4);
+    };
+
+    UnitRegs ra, rb;
+    const bool active = wu0 < wu1;
+    if (active)
+        issue(wu0, ra);  // weights are in flight while the activations are staged
+
+    // ---- stage the activations global -> LDS by DMA (no registers, all loads in flight at once): 16-byte slot p
+    //      of the buffer holds, for row m = p / chunks, the chunk whose index is p % chunks with its low four
+    //      bits XORed with m (the swizzle is its own inverse).  Rows past M repeat row M-1: their outputs are
+    //      never stored.
+    {
+        typedef __attribute__((address_space(3))) void lds_ptr_t;
+        typedef __attribute__((address_space(1))) const void global_ptr_t;
+        const int chunks = Ls >> 3;
+        const int per_thread = ROWS * chunks / kThreads;  // ROWS * chunks is a multiple of 256
+        for (int j = 0; j < per_thread; ++j) {
+            const int p = j * kThreads + tid;
+            const int m = p / chunks;
+            const int pc = p - m * chunks;
+            const int c = (pc & ~15) | ((pc ^ m) & 15);
+            const half_t *src = a.x + (size_t)min(m, a.M - 1) * a.K + kbeg + c * 8;
+            __builtin_amdgcn_global_load_lds((global_ptr_t *)src,
+                                             (lds_ptr_t *)(smem + (size_t)(j * kThreads + wave * 64) * 16), 16, 0, 0);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the DMA is not ordered against LDS reads by the compiler
+    }
+    __syncthreads();
+
+    float4_t acc[TM][4];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            acc[i][t] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    const PairMagic magic;
+
+    auto consume = [&](int u, const UnitRegs &r) {
+        uint32_t nz[4], ss[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const uint32_t z = (r.zb >> (4 * t)) & 15u;
+            nz[t] = 0xD400E400u | z | (z << 20);
+            const uint32_t pair = t < 2 ? r.sc.x : r.sc.y;
+            const uint32_t sb = (t & 1) ? (pair >> 16) : (pair & 0xffffu);
+            ss[t] = sb | (sb << 16);
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint32_t w[4] = {r.w[s].x, r.w[s].y, r.w[s].z, r.w[s].w};
+            half8_t b[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                b[t] = dequant_word(w[t], magic, nz[t], ss[t]);
+            const int c = ((u - u0) * 4 + s) * 4 + kg;  // 16-byte chunk of the activation row
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int m = 16 * i + cq;  // the A operand lane holds row lane % 16
+                const int pc = (c & ~15) | ((c ^ m) & 15);
+                const half8_t av = *reinterpret_cast<const half8_t *>(xs + (size_t)m * Ls + pc * 8);
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b[t], acc[i][t], 0, 0, 0);
+            }
+        }
+    };
+
+    if (active) {
+        // software pipeline over two register sets: the next unit's weights fly while this one is consumed
+        int u = wu0;
+        while (true) {
+            bool more = u + 1 < wu1;
+            if (more)
+                issue(u + 1, rb);
+            consume(u, ra);
+            if (!more)
+                break;
+            ++u;
+            more = u + 1 < wu1;
+            if (more)
+                issue(u + 1, ra);
+            consume(u, rb);
+            if (!more)
+                break;
+            ++u;
+        }
+    }
+
+    // ---- reduce over the four wavefronts through LDS (the activation buffer is reused) ----
+    // lane holds, for block i, n-block t, register r: row 16*i + 4*kg + r, column 4*cq + t
+    __syncthreads();
+    float *red = reinterpret_cast<float *>(smem);  // [kWaves][ROWS][kCols]
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = 16 * i + 4 * kg + r;
+            float4_t v = {acc[i][0][r], acc[i][1][r], acc[i][2][r], acc[i][3][r]};
+            *reinterpret_cast<float4_t *>(red + ((size_t)wave * ROWS + row) * kCols + 4 * cq) = v;
+        }
+    __syncthreads();
+    for (int i = tid; i < a.M * kCols; i += kThreads) {
+        const int m = i / kCols;
+        const int col = i - m * kCols;
+        const int n = tile * kCols + col;
+        float s = red[(size_t)m * kCols + col];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w)
+            s += red[((size_t)w * ROWS + m) * kCols + col];
+        if (n < N) {
+            if (a.split_k == 1)
+                a.out[(size_t)m * N + n] = (half_t)s;
+            else
+                store_device_scope(a.partial + ((size_t)slice * a.M + m) * N + n, s);
+        }
+    }
+
+    // ---- combine the K slices: the last workgroup of this column tile adds them in slice order ----
+    if (a.split_k > 1) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);  // every partial store of this workgroup has been acknowledged
+        __syncthreads();
+        if (tid == 0) {
+            const unsigned prev =
+                __hip_atomic_fetch_add(a.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = (prev == (unsigned)(a.split_k - 1));
+        }
+        __syncthreads();
+        if (s_last) {
+            for (int i = tid; i < a.M * kCols; i += kThreads) {
+                const int m = i / kCols;
+                const int n = tile * kCols + (i - m * kCols);
+                if (n < N) {
+                    float s = 0.f;
+                    for (int sl0 = 0; sl0 < a.split_k; sl0 += 8) {
+                        float v[8];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const int sl = min(sl0 + j, a.split_k - 1);
+                            v[j] = load_device_scope(a.partial + ((size_t)sl * a.M + m) * N + n);
+                        }
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            s += (sl0 + j < a.split_k) ? v[j] : 0.f;
+                    }
+                    a.out[(size_t)m * N + n] = (half_t)s;
+                }
+            }
+            if (tid == 0)
+                __hip_atomic_store(a.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+}  // namespace skinny
+}  // namespace gptq

@@ -76,7 +76,7 @@ def test_plan_validation(lib):
     from paper_2511_19438_amd import binding
 
     p = ctypes.c_void_p(0x1000)
-    bad = binding.Plan(kernel=3)
+    bad = binding.Plan(kernel=4)
     assert lib.gptq_w4a16_gemm_plan(p, p, p, p, None, p, 1, 128, 8, 128, None, ctypes.byref(bad)) == -1
     bad = binding.Plan(flags=1)
     assert lib.gptq_w4a16_gemm_plan(p, p, p, p, None, p, 1, 128, 8, 128, None, ctypes.byref(bad)) == -1

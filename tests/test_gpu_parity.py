@@ -203,9 +203,49 @@ def test_mfma_kernel_also_serves_small_batches_when_asked(B):
     assert_within_band(out, ref, "mfma M=3")
 
 
+# ------------------------------------------------------------------ GEMM, small-batch MFMA kernel
+
+SKINNY_SHAPES = [
+    # (K, N, group): several column tiles with a ragged last one, several K slices, units not a multiple of 4
+    (1024, 200, 128),
+    (2048, 1032, 128),
+    (640, 72, 128),
+    (1536, 328, 256),
+    (128, 8, 128),
+]
+
+
+@pytest.mark.parametrize("M", [1, 5, 8, 16, 17, 32, 33, 64])
+@pytest.mark.parametrize("K,N,group", SKINNY_SHAPES)
+def test_small_batch_mfma_kernel_matches_oracle(B, M, K, N, group):
+    case = workloads.make_case(M, K, N, group, seed=3 * K + N + M)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    out = run_gemm(B, case, group, B.Plan(kernel=3))
+    assert_within_band(out, ref, f"small-batch M={M} K={K} N={N} g={group}")
+
+
+@pytest.mark.parametrize("split_k", [1, 2, 3, 5, 16])
+@pytest.mark.parametrize("M", [8, 40])
+def test_small_batch_mfma_kernel_splits(B, split_k, M):
+    K, N, group = 2048, 776, 128
+    case = workloads.make_case(M, K, N, group, seed=177 + M)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    out = run_gemm(B, case, group, B.Plan(kernel=3, split_k=split_k))
+    assert_within_band(out, ref, f"small-batch split={split_k} M={M}")
+
+
+def test_small_batch_request_falls_back_when_unsupported(B):
+    # act-order and group sizes that are not multiples of 128 are served by the other kernels
+    for M, K, N, group, act in [(8, 512, 136, 64, False), (8, 512, 136, 128, True), (100, 512, 136, 128, False)]:
+        case = workloads.make_case(M, K, N, group, seed=M + N, act_order=act)
+        ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], case["g_idx"], group)
+        out = run_gemm(B, case, group, B.Plan(kernel=3))
+        assert_within_band(out, ref, f"fallback M={M} g={group} act={act}")
+
+
 # ------------------------------------------------------------------ exactness pins in the GEMM kernels themselves
 
-@pytest.mark.parametrize("M,plan_kernel", [(1, 1), (4, 1), (8, 1), (16, 1), (40, 2), (300, 2)])
+@pytest.mark.parametrize("M,plan_kernel", [(1, 1), (4, 1), (8, 1), (16, 1), (40, 2), (300, 2), (8, 3), (40, 3)])
 @pytest.mark.parametrize("act", [False, True])
 def test_one_hot_rows_return_weight_rows_bit_exact(B, M, plan_kernel, act):
     K, N, group = 1024, 264, 128
@@ -239,8 +279,8 @@ def test_codes_equal_to_zero_points_give_zero(B, M):
             "scales": np.full((K // group, N), 0.01, np.float16), "g_idx": None,
             "x": workloads.make_activations(M, K, seed=4)}
     out = run_gemm(B, case, group)
-    if M >= 8:
-        # per-element dequantisation (large batches, MFMA): every weight is exactly zero
+    if M >= 3:
+        # per-element dequantisation (MFMA kernels): every weight is exactly zero
         assert np.all(out == 0)
     else:
         # small batches contract the biased codes (1024 + q) and take the bias and the zero point off per
