@@ -98,6 +98,17 @@ GPTQ_API int gptq_w4a16_gemm_plan(const void *x, const void *qweight, const void
                          gptq_stream_t stream, const gptq_w4a16_plan_t *plan);
 
 /*
+ * Host-only: what gptq_w4a16_gemm_plan(..., request) would run for a problem of this shape.
+ * `act_order` non-zero means a g_idx array would be passed; `request` may be NULL (automatic).
+ * On success *resolved holds the kernel id (1, 2 or 3, never 0), its K split (1 for the big-tile MFMA
+ * kernel) and its tile (vector kernel: columns per workgroup; big-tile MFMA kernel: tile id;
+ * small-batch MFMA kernel: 0).  Touches no device.  Errors as for gptq_w4a16_gemm_plan's
+ * shape and plan checks.
+ */
+GPTQ_API int gptq_w4a16_plan_query(int M, int K, int N, int group_size, int act_order,
+                                   const gptq_w4a16_plan_t *request, gptq_w4a16_plan_t *resolved);
+
+/*
  * The dequantised weights themselves: w_out (fp16 [K, N], device) = W as defined above,
  * computed as the exact integer difference q - z followed by ONE IEEE fp16 multiplication
  * by the scale (round to nearest even, subnormals kept).  Bit-exact by definition.

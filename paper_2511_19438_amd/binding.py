@@ -33,7 +33,7 @@ class Plan(ctypes.Structure):
                 ("flags", ctypes.c_int), ("reserved", ctypes.c_int * 4)]
 
 
-EXPORTS = ("gptq_w4a16_gemm", "gptq_w4a16_gemm_plan", "gptq_w4a16_dequant", "gptq_w4a16_unpack",
+EXPORTS = ("gptq_w4a16_gemm", "gptq_w4a16_gemm_plan", "gptq_w4a16_plan_query", "gptq_w4a16_dequant", "gptq_w4a16_unpack",
            "gptq_w4a16_workspace_bytes", "gptq_w4a16_set_workspace", "gptq_w4a16_strerror", "gptq_w4a16_version")
 
 
@@ -52,6 +52,8 @@ def load() -> ctypes.CDLL:
     lib.gptq_w4a16_gemm.restype = ci
     lib.gptq_w4a16_gemm_plan.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, vp, ctypes.POINTER(Plan)]
     lib.gptq_w4a16_gemm_plan.restype = ci
+    lib.gptq_w4a16_plan_query.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(Plan), ctypes.POINTER(Plan)]
+    lib.gptq_w4a16_plan_query.restype = ci
     lib.gptq_w4a16_dequant.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, vp]
     lib.gptq_w4a16_dequant.restype = ci
     lib.gptq_w4a16_unpack.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp]
@@ -154,6 +156,17 @@ def gptq_w4a16_unpack(qweight, q_out, qzeros, z_out, group_size: int):
     if rc != 0:
         raise GptqError(rc, "gptq_w4a16_unpack")
     return q_out, z_out
+
+
+def gptq_w4a16_plan_query(M: int, K: int, N: int, group_size: int, act_order: bool = False,
+                          plan: Optional["Plan"] = None) -> "Plan":
+    """The plan a GEMM call of this shape resolves to (host only, touches no device)."""
+    out = Plan()
+    rc = load().gptq_w4a16_plan_query(int(M), int(K), int(N), int(group_size), int(bool(act_order)),
+                                      ctypes.byref(plan) if plan is not None else None, ctypes.byref(out))
+    if rc != 0:
+        raise GptqError(rc, "gptq_w4a16_plan_query")
+    return out
 
 
 def gptq_w4a16_workspace_bytes(M: int, K: int, N: int, group_size: int) -> int:

@@ -1,6 +1,8 @@
 // Host side of the split-K vector kernel: launch plan, scratch sizing, dispatch on batch size.
 #include "decode_kernel.h"
 
+#include <cmath>
+
 namespace gptq {
 
 namespace {
@@ -36,12 +38,43 @@ Derived derive(const Problem &p, int cols_per_wg, int chunk_rows)
     d.tiles_n = ceil_div(p.N, cols_per_wg);
     const int mb = batch_template(p.M < 16 ? p.M : 16);
     int ls_max = kMaxSliceLdsBytes / (2 * mb);  // activations per batch row per slice
-    if (ls_max > 8192)
-        ls_max = 8192;
+    if (ls_max > 16384)
+        ls_max = 16384;
     d.max_chunks_per_slice = ls_max / (chunk_rows * 8);
     if (d.max_chunks_per_slice < 1)
         d.max_chunks_per_slice = 1;
     return d;
+}
+
+// Estimated duration (microseconds) of one launch with the given column tile and chunks per slice.
+//
+// The kernel is bound by whichever is slower: the HBM stream of the packed weights, or the most loaded
+// compute unit (workgroups are dealt out evenly, so that is ceil(workgroups / 256) workgroups' worth of
+// dequantisation arithmetic); narrow tiles read short row segments and stream below the full rate, a
+// K split adds the scratch round trip of the combine step, and more workgroups than compute units
+// cost a little extra.  The constants were fitted to measurements of the Llama-7B/70B projection
+// shapes at M = 1 on MI355X; the arithmetic rate is scaled by the instruction count per packed word.
+double estimate_us(const Problem &p, const Derived &d, int cols_per_wg, int chunk_rows, int cps, bool act)
+{
+    const int m = p.M < 16 ? p.M : 16;
+    const double weight_bytes = 0.5 * (double)p.K * (double)p.N;
+    const int slices = ceil_div(d.total_chunks, cps);
+    const double wgs = (double)d.tiles_n * slices;
+    const double tb_per_s = cols_per_wg <= 16 ? 2.6 : cols_per_wg <= 32 ? 5.0 : cols_per_wg <= 64 ? 5.8 : 6.2;
+    const double hbm = weight_bytes / (tb_per_s * 1e6);
+    double ops = m < 8 ? 11.0 + 8.0 * (m - 1) : 30.0 + 8.0 * m;  // vector instructions per packed word
+    if (act)
+        ops += 24.0;
+    const double cu_gb_per_s = 44.0 * 11.0 / ops;
+    const double wg_bytes = 0.5 * (double)cps * chunk_rows * 8 * cols_per_wg;
+    const double rounds = (double)ceil_div((int)wgs, 256);
+    const double cu = rounds * (wg_bytes / (cu_gb_per_s * 1e3) + 0.3);  // 0.3 us of staging and reduction each
+    double t = 4.2 + std::cbrt(hbm * hbm * hbm + cu * cu * cu);
+    if (slices > 1)
+        t += 0.8;
+    if (wgs > 256.0)
+        t += 0.03 * hbm;
+    return t;
 }
 
 }  // namespace
@@ -54,51 +87,65 @@ void decode_make_plan(const Problem &p, DecodePlan &plan)
     const bool fixed_shape = act || plan.chunk_rows != 4;  // these variants exist for 64-column tiles only
     const int c = plan.cols_per_wg;
     const bool tile_given = (c == 16 || c == 32 || c == 64 || c == 128 || c == 256) && !fixed_shape;
-    if (!tile_given) {
-        // widest tile that still leaves at least ~512 column tiles' worth of workgroups to spread
-        plan.cols_per_wg = 64;
-        if (!fixed_shape) {
-            if (ceil_div(p.N, 64) > 768)
-                plan.cols_per_wg = 128;
-            if (ceil_div(p.N, 128) > 768)
-                plan.cols_per_wg = 256;
-        }
-    }
-    while (!fixed_shape && plan.cols_per_wg < 256 && ceil_div(p.N, plan.cols_per_wg) > kMaxColumnTiles)
-        plan.cols_per_wg *= 2;  // keep one arrival counter per column tile inside the fixed counter area
-    const Derived d = derive(p, plan.cols_per_wg, plan.chunk_rows);
 
-    const int step_chunks = d.rw * (act ? 1 : 2);  // chunks one workgroup consumes per pipeline step
-    int cps;
-    if (plan.split_k > 0) {
-        int split = plan.split_k < d.total_chunks ? plan.split_k : d.total_chunks;
-        cps = ceil_div(d.total_chunks, split);
-    } else {
-        // Slices are whole pipeline steps (no lane idles or re-reads a clamped chunk) and their number puts
-        // the workgroup count as close as possible (in ratio) to two per compute unit.
-        const double target_wgs = 512.0;
-        int best_cps = 0;
-        double best_cost = 0.0;
+    // candidates: every allowed tile width (one arrival counter per column tile must fit the fixed
+    // counter area) and, per width, every slice length of whole pipeline steps (no lane idles or re-reads
+    // a clamped chunk); the cheapest by the estimate wins
+    int best_tile = 0, best_cps = 0;
+    double best_t = 0.0;
+    for (int tile = 32; tile <= 256; tile *= 2) {
+        if (tile_given && tile != c)
+            continue;
+        if (fixed_shape && tile != 64)
+            continue;
+        if (ceil_div(p.N, tile) > kMaxColumnTiles && tile < 256)
+            continue;
+        const Derived d = derive(p, tile, plan.chunk_rows);
+        const int step_chunks = d.rw * (act ? 1 : 2);  // chunks one workgroup consumes per pipeline step
         const int max_steps = ceil_div(d.total_chunks, step_chunks);
+        if (plan.split_k > 0) {
+            const int split = plan.split_k < d.total_chunks ? plan.split_k : d.total_chunks;
+            int cps = ceil_div(d.total_chunks, split);
+            if (cps > d.max_chunks_per_slice)
+                cps = d.max_chunks_per_slice;
+            const double t = estimate_us(p, d, tile, plan.chunk_rows, cps, act);
+            if (!best_tile || t < best_t) {
+                best_tile = tile, best_cps = cps, best_t = t;
+            }
+            continue;
+        }
+        int last_slices = 0;
         for (int steps = 1; steps <= max_steps; ++steps) {
-            const int c = steps * step_chunks;
-            if (c > d.max_chunks_per_slice && best_cps)
-                break;
-            const double wgs = (double)d.tiles_n * ceil_div(d.total_chunks, c);
-            const double ratio = wgs > target_wgs ? wgs / target_wgs : target_wgs / wgs;
-            if (!best_cps || ratio < best_cost - 1e-9) {
-                best_cps = c;
-                best_cost = ratio;
+            int cps = steps * step_chunks;
+            if (cps > d.max_chunks_per_slice) {
+                if (steps > 1)
+                    break;
+                cps = d.max_chunks_per_slice;
+            }
+            const int slices = ceil_div(d.total_chunks, cps);
+            if (slices == last_slices)
+                continue;  // same slice count as with the shorter slices before: only less balanced
+            last_slices = slices;
+            const double t = estimate_us(p, d, tile, plan.chunk_rows, cps, act);
+            if (!best_tile || t < best_t - 1e-9) {
+                best_tile = tile, best_cps = cps, best_t = t;
             }
         }
-        cps = best_cps;
     }
-    if (cps > d.max_chunks_per_slice)
-        cps = d.max_chunks_per_slice;
-    if (cps < 1)
-        cps = 1;
-    plan.chunks_per_slice = cps;
-    plan.split_k = ceil_div(d.total_chunks, cps);
+    if (tile_given && c == 16) {  // the narrowest tile is never chosen, only honoured
+        const Derived d = derive(p, 16, plan.chunk_rows);
+        const int split = plan.split_k > 0 ? (plan.split_k < d.total_chunks ? plan.split_k : d.total_chunks) : 1;
+        best_tile = 16;
+        best_cps = ceil_div(d.total_chunks, split);
+        if (best_cps > d.max_chunks_per_slice)
+            best_cps = d.max_chunks_per_slice;
+    }
+    if (best_cps < 1)
+        best_cps = 1;
+    plan.cols_per_wg = best_tile;
+    const Derived d = derive(p, plan.cols_per_wg, plan.chunk_rows);
+    plan.chunks_per_slice = best_cps;
+    plan.split_k = ceil_div(d.total_chunks, best_cps);
 }
 
 size_t decode_counter_bytes(int)

@@ -170,56 +170,83 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
     int *gl = reinterpret_cast<int *>(smem + off);                      // ACT: [Ls] group of each k
     uint32_t *tab = reinterpret_cast<uint32_t *>(smem + off + (ACT ? (size_t)Ls * sizeof(int) : 0));  // ACT: [groups][CT]
 
-    // Every load below is made unconditional by clamping its chunk / row to the last valid one of the
-    // slice; what a clamped (out-of-range) chunk contributes is zeroed when it is used.
+    // Every load below is made unconditional by clamping its chunk / column to the last valid one of the
+    // slice; what a clamped (out-of-range) chunk contributes is zeroed when it is used.  No branch sits
+    // between a load and its use, so the waits the compiler inserts count exactly the loads that were
+    // issued later and the prefetched step stays in flight.
+    //
+    // Addresses are a wavefront-uniform base (scalar registers) plus a 32-bit byte offset per lane, so a
+    // load costs no 64-bit vector arithmetic: the R packed rows of a chunk differ only in the base.
+    const int n0c = min(n0, N - 4);
+    const uint32_t *wslice = a.qweight + (size_t)c0 * R * N;  // first packed row of the slice
+    auto lane_chunk = [&](int t, int j) { return t * STEP + j * RW + rid; };  // slice-relative, step t
     using Regs = StepRegs<R, UNROLL>;
-    auto issue = [&](int u0, Regs &r) {
+    auto issue = [&](int t, Regs &r) {
 #pragma unroll
         for (int j = 0; j < UNROLL; ++j) {
-            const int u = min(u0 + j * RW, c1 - 1);
+            const int ul = min(lane_chunk(t, j), nchunks - 1);
+            const uint32_t woff = (__umul24(ul * R, N) + n0c) * 4u;
 #pragma unroll
-            for (int rr = 0; rr < R; ++rr) {
-                const int row = min(u * R + rr, a.rows - 1);
-                r.wq[j][rr] = *reinterpret_cast<const uint4 *>(a.qweight + (size_t)row * N + n0);
-            }
+            for (int rr = 0; rr < R; ++rr)
+                r.wq[j][rr] = *reinterpret_cast<const uint4 *>(
+                    reinterpret_cast<const char *>(wslice + (size_t)rr * N) + woff);
             if (!ACT) {
+                const int u = c0 + ul;
                 const int grp = a.chunk_group_shift >= 0 ? (u >> a.chunk_group_shift) : (u * R) / a.rows_per_group;
-                r.sc[j] = *reinterpret_cast<const half4_t *>(a.scales + (size_t)grp * N + n0);
-                r.zb[j] = a.qzeros[(size_t)grp * (N >> 3) + (n0 >> 3)] >> ((n0 & 4) * 4);
+                r.sc[j] = *reinterpret_cast<const half4_t *>(reinterpret_cast<const char *>(a.scales) +
+                                                             (__umul24(grp, N) + n0c) * 2u);
+                // the shift that isolates this lane's zero points is applied when the word is used: no wait here
+                r.zb[j] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(a.qzeros) +
+                                                              (__umul24(grp, N >> 3) + (n0c >> 3)) * 4u);
             }
         }
     };
 
-    const bool active = n0 < N && c0 + rid < c1;  // this lane owns real columns and at least one chunk
-    Regs ra, rb;
-    if (active)
-        issue(c0 + rid, ra);  // weights are in flight while the activations are staged
+    const int zshift = (n0c & 4) * 4;  // this lane's four zero points inside the packed word
 
-    // ---- stage the activations of this slice (128-bit loads), one chunk of R packed rows per thread and
-    //      turn, each group of eight stored in the order (0,4,1,5,2,6,3,7) that the dequantised pairs need ----
-    {
-        for (int i = tid; i < MB * nchunks; i += kThreads) {
-            const int m = MB == 1 ? 0 : i / nchunks;
-            const int ch = i - m * nchunks;
-            float s_lo = 0.f, s_hi = 0.f;  // sums of x over the k that get bias 1024 / bias 64
-#pragma unroll
-            for (int rr = 0; rr < R; ++rr) {
-                const int kk = (ch * R + rr) * 8;  // offset inside the slice
-                if (kk < Ls) {
-                    half8_t h = {0, 0, 0, 0, 0, 0, 0, 0};
-                    if (m < a.M)
-                        h = *reinterpret_cast<const half8_t *>(a.x + (size_t)m * a.K + kbeg + kk);
-                    half8_t p = {h[0], h[4], h[1], h[5], h[2], h[6], h[3], h[7]};
-                    *reinterpret_cast<half8_t *>(xs + (size_t)m * Ls + kk) = p;
-                    if (FACTORED) {
-                        s_lo += ((float)h[0] + (float)h[4]) + ((float)h[2] + (float)h[6]);
-                        s_hi += ((float)h[1] + (float)h[5]) + ((float)h[3] + (float)h[7]);
-                    }
-                }
-            }
-            if (FACTORED)
-                xc[(size_t)m * nchunks + ch] = make_float2(1024.f * s_lo + 64.f * s_hi, s_lo + s_hi);
+    // ---- stage the activations of this slice: one packed row (eight values, one 128-bit load) per thread
+    //      and turn, stored in the order (0,4,1,5,2,6,3,7) that the dequantised pairs need.  The first
+    //      turn's load goes out before the weights' and is waited for alone. ----
+    const int rows_s = Ls >> 3;            // packed rows of the slice
+    const int rows_p = nchunks * R;        // the same, padded to whole chunks
+    const int items = MB * rows_p;
+    auto x_load = [&](int i) -> half8_t {
+        const int m = MB == 1 ? 0 : i / rows_p;
+        const int row = i - m * rows_p;
+        const half_t *src = a.x + (size_t)min(m, a.M - 1) * a.K + kbeg + min(row, rows_s - 1) * 8;
+        return *reinterpret_cast<const half8_t *>(src);
+    };
+    auto x_store = [&](int i, half8_t h) {
+        const int m = MB == 1 ? 0 : i / rows_p;
+        const int row = i - m * rows_p;
+        const bool real = i < items && row < rows_s && m < a.M;
+        if (!real)
+            h = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+        if (i < items && row < rows_s) {
+            half8_t p = {h[0], h[4], h[1], h[5], h[2], h[6], h[3], h[7]};
+            *reinterpret_cast<half8_t *>(xs + (size_t)m * Ls + row * 8) = p;
         }
+        if (FACTORED) {
+            // sums of x over the k that get bias 1024 / bias 64, added over the R rows of the chunk
+            float s_lo = ((float)h[0] + (float)h[4]) + ((float)h[2] + (float)h[6]);
+            float s_hi = ((float)h[1] + (float)h[5]) + ((float)h[3] + (float)h[7]);
+#pragma unroll
+            for (int o = 1; o < R; o <<= 1) {
+                s_lo += __shfl_xor(s_lo, o, 64);
+                s_hi += __shfl_xor(s_hi, o, 64);
+            }
+            if (i < items && (row & (R - 1)) == 0)
+                xc[(size_t)m * nchunks + row / R] = make_float2(1024.f * s_lo + 64.f * s_hi, s_lo + s_hi);
+        }
+    };
+
+    Regs ra, rb;
+    {
+        const half8_t h0 = x_load(tid);
+        issue(0, ra);  // the weights are in flight while the activations are staged
+        x_store(tid, h0);
+        for (int i0 = kThreads; i0 < items; i0 += kThreads)
+            x_store(i0 + tid, x_load(i0 + tid));
         if (ACT) {
             for (int i = tid; i < Ls; i += kThreads)
                 gl[i] = a.g_idx[kbeg + i];
@@ -249,18 +276,19 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
     const NibbleMagic magic;
 
     // dequantise and contract the chunks held in `r`
-    auto consume = [&](int u0, const Regs &r) {
+    auto consume = [&](int t, const Regs &r) {
 #pragma unroll
         for (int j = 0; j < UNROLL; ++j) {
-            const bool valid = u0 + j * RW < c1;
-            const int u = min(u0 + j * RW, c1 - 1);
+            const bool valid = lane_chunk(t, j) < nchunks;
+            const int ul = min(lane_chunk(t, j), nchunks - 1);
+            const half_t *xchunk = xs + ul * (R * 8);  // this chunk's activations; batch row m at + m * Ls
             half2_t neg_lo[4], neg_hi[4], s2[4];
             float sf[4], zf[4];
             float gacc[MB][4];
             if (!ACT) {
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    const uint32_t z = (r.zb[j] >> (4 * c)) & 15u;
+                    const uint32_t z = (r.zb[j] >> (zshift + 4 * c)) & 15u;
                     const half_t s = valid ? r.sc[j][c] : (half_t)0;  // a clamped chunk contributes nothing
                     if (FACTORED) {
                         zf[c] = (float)z;
@@ -281,9 +309,6 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
             }
 #pragma unroll
             for (int rr = 0; rr < R; ++rr) {
-                const bool row_valid = valid && (u * R + rr < a.rows);
-                const int row = min(u * R + rr, a.rows - 1);
-                const int koff = row * 8 - kbeg;
                 const uint32_t w[4] = {r.wq[j][rr].x, r.wq[j][rr].y, r.wq[j][rr].z, r.wq[j][rr].w};
                 half2_t d[4][4];
                 if (FACTORED) {
@@ -300,8 +325,8 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
                     }
                 } else {
                     // every k of the packed row may belong to a different group
-                    const int4 ga = *reinterpret_cast<const int4 *>(gl + koff);
-                    const int4 gb = *reinterpret_cast<const int4 *>(gl + koff + 4);
+                    const int4 ga = *reinterpret_cast<const int4 *>(gl + (ul * R + rr) * 8);
+                    const int4 gb = *reinterpret_cast<const int4 *>(gl + (ul * R + rr) * 8 + 4);
                     const int g[8] = {ga.x, ga.y, ga.z, ga.w, gb.x, gb.y, gb.z, gb.w};
                     uint4 t[8];
 #pragma unroll
@@ -322,8 +347,8 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
                 }
 #pragma unroll
                 for (int m = 0; m < MB; ++m) {
-                    uint4 xv = *reinterpret_cast<const uint4 *>(xs + (size_t)m * Ls + koff);
-                    if (ACT && !row_valid)
+                    uint4 xv = *reinterpret_cast<const uint4 *>(xchunk + m * Ls + rr * 8);
+                    if (ACT && !valid)
                         xv = make_uint4(0, 0, 0, 0);
                     const half2_t xp[4] = {as_half2(xv.x), as_half2(xv.y), as_half2(xv.z), as_half2(xv.w)};
 #pragma unroll
@@ -342,7 +367,7 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
             if (FACTORED) {
 #pragma unroll
                 for (int m = 0; m < MB; ++m) {
-                    const float2 bs = xc[(size_t)m * nchunks + (u - c0)];
+                    const float2 bs = xc[m * nchunks + ul];
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
                         const float t = __builtin_fmaf(-zf[c], bs.y, gacc[m][c] - bs.x);  // sum_k x_k (q_k - z)
@@ -353,24 +378,38 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
         }
     };
 
-    if (active) {
-        // software pipeline over two register sets: the next step's weights fly while this step is consumed
-        int u0 = c0 + rid;
-        while (true) {
-            bool more = u0 + STEP < c1;
-            if (more)
-                issue(u0 + STEP, rb);
-            consume(u0, ra);
-            if (!more)
-                break;
-            u0 += STEP;
-            more = u0 + STEP < c1;
-            if (more)
-                issue(u0 + STEP, ra);
-            consume(u0, rb);
-            if (!more)
-                break;
-            u0 += STEP;
+    {
+        // Software pipeline over two register sets: the next step's weights fly while this step is
+        // consumed.  Every wavefront runs the same number of steps (lanes past the end of the slice load
+        // clamped chunks and add nothing); the steady-state loop issues unconditionally and the last one
+        // or two steps are peeled, so that no branch separates a load from its use.
+        const int nsteps = (nchunks + STEP - 1) / STEP;
+        int t = 0;
+        // The step boundary: everything a step adds to the accumulators is computed before the loads of
+        // the step after next are issued (the empty asm orders the arithmetic, the scheduling barrier the
+        // loads), so two steps are in flight, not three, and the register count stays down.
+        auto step_boundary = [&]() {
+#pragma unroll
+            for (int m = 0; m < MB; ++m)
+                asm volatile("" : "+v"(acc[m][0]), "+v"(acc[m][1]), "+v"(acc[m][2]), "+v"(acc[m][3])::"memory");
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        while (t + 2 < nsteps) {
+            issue(t + 1, rb);
+            consume(t, ra);
+            step_boundary();
+            issue(t + 2, ra);
+            consume(t + 1, rb);
+            step_boundary();
+            t += 2;
+        }
+        if (t + 2 == nsteps) {
+            issue(t + 1, rb);
+            consume(t, ra);
+            step_boundary();
+            consume(t + 1, rb);
+        } else {
+            consume(t, ra);
         }
     }
 

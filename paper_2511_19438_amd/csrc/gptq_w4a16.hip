@@ -86,8 +86,17 @@ int acquire_workspace(size_t bytes, void **out)
 constexpr int kVectorMaxM = 2;
 constexpr int kSmallBatchAutoMaxM = 32;
 
-int run_gemm(const Problem &p, hipStream_t stream, const gptq_w4a16_plan_t *plan)
+// What a call resolves to: the kernel and its decomposition, after the automatic choices.
+struct Resolved {
+    int kernel;  // 1 vector, 2 big-tile MFMA, 3 small-batch MFMA
+    DecodePlan decode;
+    SkinnyPlan skinny;
+    PrefillPlan prefill;
+};
+
+Resolved resolve(const Problem &p, const gptq_w4a16_plan_t *plan)
 {
+    Resolved r = {};
     int kernel = plan ? plan->kernel : 0;
     if (kernel == 0) {
         if (p.M <= kVectorMaxM)
@@ -101,36 +110,51 @@ int run_gemm(const Problem &p, hipStream_t stream, const gptq_w4a16_plan_t *plan
         kernel = (p.M <= kDecodeMaxM) ? 1 : 2;
     if (kernel == 2 && !prefill_supported(p))
         kernel = 1;
-
+    r.kernel = kernel;
     if (kernel == 1) {
-        DecodePlan dp;
-        dp.cols_per_wg = plan ? plan->tile : 0;
-        dp.split_k = plan ? plan->split_k : 0;
-        dp.chunk_rows = 0;
-        dp.chunks_per_slice = 0;
-        dp.flags = 0;
-        decode_make_plan(p, dp);
+        r.decode.cols_per_wg = plan ? plan->tile : 0;
+        r.decode.split_k = plan ? plan->split_k : 0;
+        decode_make_plan(p, r.decode);
+    } else if (kernel == 3) {
+        r.skinny.split_k = plan ? plan->split_k : 0;
+        skinny_make_plan(p, r.skinny);
+    } else {
+        r.prefill.tile = plan ? plan->tile : 0;
+        prefill_make_plan(p, r.prefill);
+    }
+    return r;
+}
+
+int run_gemm(const Problem &p, hipStream_t stream, const gptq_w4a16_plan_t *plan)
+{
+    const Resolved r = resolve(p, plan);
+    if (r.kernel == 1) {
         void *ws = nullptr;
-        const int rc = acquire_workspace(decode_workspace_bytes(p, dp), &ws);
+        const int rc = acquire_workspace(decode_workspace_bytes(p, r.decode), &ws);
         if (rc != GPTQ_OK)
             return rc;
-        return launch_decode(p, dp, ws, stream) == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
+        return launch_decode(p, r.decode, ws, stream) == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
     }
-    if (kernel == 3) {
-        SkinnyPlan sp;
-        sp.split_k = plan ? plan->split_k : 0;
-        sp.units_per_slice = 0;
-        skinny_make_plan(p, sp);
+    if (r.kernel == 3) {
         void *ws = nullptr;
-        const int rc = acquire_workspace(skinny_workspace_bytes(p, sp), &ws);
+        const int rc = acquire_workspace(skinny_workspace_bytes(p, r.skinny), &ws);
         if (rc != GPTQ_OK)
             return rc;
-        return launch_skinny(p, sp, ws, stream) == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
+        return launch_skinny(p, r.skinny, ws, stream) == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
     }
-    PrefillPlan pp;
-    pp.tile = plan ? plan->tile : 0;
-    prefill_make_plan(p, pp);
-    return launch_prefill(p, pp, stream) == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
+    return launch_prefill(p, r.prefill, stream) == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
+}
+
+int check_plan(const gptq_w4a16_plan_t *plan)
+{
+    if (!plan)
+        return GPTQ_OK;
+    if (plan->kernel < 0 || plan->kernel > 3 || plan->split_k < 0 || plan->tile < 0 || plan->flags != 0)
+        return GPTQ_INVALID_ARG;
+    for (int i = 0; i < 4; ++i)
+        if (plan->reserved[i] != 0)
+            return GPTQ_INVALID_ARG;
+    return GPTQ_OK;
 }
 
 }  // namespace
@@ -146,13 +170,8 @@ int gptq_w4a16_gemm_plan(const void *x, const void *qweight, const void *qzeros,
     const int rc = check_shape(K, N, group_size);
     if (rc != GPTQ_OK)
         return rc;
-    if (plan) {
-        if (plan->kernel < 0 || plan->kernel > 3 || plan->split_k < 0 || plan->tile < 0 || plan->flags != 0)
-            return GPTQ_INVALID_ARG;
-        for (int i = 0; i < 4; ++i)
-            if (plan->reserved[i] != 0)
-                return GPTQ_INVALID_ARG;
-    }
+    if (check_plan(plan) != GPTQ_OK)
+        return GPTQ_INVALID_ARG;
     if (!aligned16(x) || !aligned16(qweight) || !aligned16(qzeros) || !aligned16(scales) || !aligned16(out) ||
         (g_idx && !aligned16(g_idx)))
         return GPTQ_MISALIGNED;
@@ -174,6 +193,39 @@ int gptq_w4a16_gemm(const void *x, const void *qweight, const void *qzeros, cons
                     const void *g_idx, void *out, int M, int K, int N, int group_size, gptq_stream_t stream)
 {
     return gptq_w4a16_gemm_plan(x, qweight, qzeros, scales, g_idx, out, M, K, N, group_size, stream, nullptr);
+}
+
+int gptq_w4a16_plan_query(int M, int K, int N, int group_size, int act_order, const gptq_w4a16_plan_t *request,
+                          gptq_w4a16_plan_t *resolved)
+{
+    if (!resolved || M <= 0)
+        return GPTQ_INVALID_ARG;
+    const int rc = check_shape(K, N, group_size);
+    if (rc != GPTQ_OK)
+        return rc;
+    if (check_plan(request) != GPTQ_OK)
+        return GPTQ_INVALID_ARG;
+    static const int32_t some_g_idx = 0;  // only its presence matters to the plan
+    Problem p = {};
+    p.g_idx = act_order ? &some_g_idx : nullptr;
+    p.M = M;
+    p.K = K;
+    p.N = N;
+    p.group_size = group_size;
+    const Resolved r = resolve(p, request);
+    gptq_w4a16_plan_t out = {};
+    out.kernel = r.kernel;
+    if (r.kernel == 1) {
+        out.split_k = r.decode.split_k;
+        out.tile = r.decode.cols_per_wg;
+    } else if (r.kernel == 3) {
+        out.split_k = r.skinny.split_k;
+    } else {
+        out.split_k = 1;
+        out.tile = r.prefill.tile;
+    }
+    *resolved = out;
+    return GPTQ_OK;
 }
 
 int gptq_w4a16_dequant(const void *qweight, const void *qzeros, const void *scales, const void *g_idx,

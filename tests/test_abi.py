@@ -27,9 +27,10 @@ def declared_functions():
 
 def test_header_declares_the_expected_entry_points():
     names = declared_functions()
-    assert len(names) == len(set(names)) == 8
+    assert len(names) == len(set(names)) == 9
     for required in ("gptq_w4a16_gemm", "gptq_w4a16_dequant", "gptq_w4a16_unpack", "gptq_w4a16_workspace_bytes",
-                     "gptq_w4a16_set_workspace", "gptq_w4a16_strerror", "gptq_w4a16_version"):
+                     "gptq_w4a16_set_workspace", "gptq_w4a16_strerror", "gptq_w4a16_version",
+                     "gptq_w4a16_gemm_plan", "gptq_w4a16_plan_query"):
         assert required in names
 
 
@@ -93,3 +94,65 @@ def test_workspace_bytes_is_host_only_and_monotone_in_batch(lib):
     assert f(0, 4096, 4096, 128) == 0
     # partial sums of the K slices in fp32 stay a small fraction of the packed weights
     assert f(1, 4096, 4096, 128) < 4096 * 4096 // 2 // 4
+
+
+# ---- host logic of the launch plans (no device is touched) ----
+
+def test_default_dispatch_by_batch_size(lib):
+    from paper_2511_19438_amd import binding
+
+    q = binding.gptq_w4a16_plan_query
+    assert [q(M, 4096, 4096, 128).kernel for M in (1, 2, 3, 16, 32, 33, 2048)] == [1, 1, 3, 3, 3, 2, 2]
+    # act-order and group sizes the small-batch MFMA kernel does not take fall back
+    assert q(8, 4096, 4096, 128, act_order=True).kernel == 1
+    assert q(24, 4096, 4096, 128, act_order=True).kernel == 2
+    assert q(8, 4096, 4096, 64).kernel == 1
+    # an explicit request is honoured where the kernel supports the problem
+    assert q(1, 4096, 4096, 128, plan=binding.Plan(kernel=2)).kernel == 2
+    assert q(64, 4096, 4096, 128, plan=binding.Plan(kernel=3)).kernel == 3
+    assert q(8, 4096, 4096, 128, act_order=True, plan=binding.Plan(kernel=3)).kernel == 1
+
+
+def test_vector_plan_is_well_formed_for_every_shape(lib):
+    """Tile widths come from the supported set, slices are whole pipeline steps and never exceed the LDS budget."""
+    from paper_2511_19438_amd import binding, workloads
+
+    shapes = [(s.K, s.N) for s in workloads.LLAMA_7B + workloads.LLAMA_70B] + [(128, 8), (256, 24), (4096, 11008), (65536, 512)]
+    for (K, N) in shapes:
+        for M in (1, 2, 4, 8, 16):
+            for act in (False, True):
+                pl = binding.gptq_w4a16_plan_query(M, K, N, 128, act_order=act, plan=binding.Plan(kernel=1))
+                assert pl.kernel == 1
+                assert pl.tile in (32, 64, 128, 256) and (not act or pl.tile == 64)
+                chunks = K // 32
+                assert 1 <= pl.split_k <= chunks
+                per_slice = -(-chunks // pl.split_k) * 32  # activations per row and slice (upper bound)
+                assert per_slice * 2 * M <= 2 * 32 * 1024 + 4096 or pl.split_k == chunks
+    # explicit requests are kept
+    pl = binding.gptq_w4a16_plan_query(1, 4096, 4096, 128, plan=binding.Plan(kernel=1, tile=16, split_k=2))
+    assert (pl.tile, pl.split_k) == (16, 2)
+    pl = binding.gptq_w4a16_plan_query(1, 4096, 4096, 128, plan=binding.Plan(kernel=1, tile=256))
+    assert pl.tile == 256
+
+
+def test_vector_plan_prefers_one_slice_per_compute_unit_on_wide_layers(lib):
+    """Wide layers at M = 1 get at most one workgroup per compute unit and no K split (no combine step)."""
+    from paper_2511_19438_amd import binding
+
+    for (K, N) in ((4096, 12288), (4096, 22016), (8192, 57344)):
+        pl = binding.gptq_w4a16_plan_query(1, K, N, 128)
+        assert pl.split_k == 1 and -(-N // pl.tile) <= 256, (K, N, pl.tile, pl.split_k)
+    # a narrow, deep layer needs the K split to fill the chip
+    pl = binding.gptq_w4a16_plan_query(1, 11008, 4096, 128)
+    assert pl.split_k > 1 and 128 <= -(-4096 // pl.tile) * pl.split_k <= 512
+
+
+def test_plan_query_validates_like_the_gemm(lib):
+    from paper_2511_19438_amd import binding
+
+    with pytest.raises(binding.GptqError):
+        binding.gptq_w4a16_plan_query(0, 4096, 4096, 128)
+    with pytest.raises(binding.GptqError):
+        binding.gptq_w4a16_plan_query(1, 4100, 4096, 128)
+    with pytest.raises(binding.GptqError):
+        binding.gptq_w4a16_plan_query(1, 4096, 4096, 128, plan=binding.Plan(kernel=7))

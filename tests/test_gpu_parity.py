@@ -152,6 +152,18 @@ def test_decode_plans_match_oracle(B, tile, split_k, M):
     assert_within_band(out, ref, f"plan tile={tile} split={split_k} M={M}")
 
 
+@pytest.mark.parametrize("M,K,split_k", [(1, 11008, 1), (2, 11008, 1), (1, 16384, 1), (1, 16416, 1), (2, 16384, 3)])
+def test_decode_deep_slices(B, M, K, split_k):
+    """One workgroup walks the whole K (or the longest slice the LDS budget allows): many pipeline steps,
+    a ragged last step, the activations of the slice filling the staging buffer."""
+    N, group = 264, 32
+    case = workloads.make_case(M, K, N, group, seed=K + M)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    for tile in (32, 128):
+        out = run_gemm(B, case, group, B.Plan(kernel=1, split_k=split_k, tile=tile))
+        assert_within_band(out, ref, f"deep slice M={M} K={K} tile={tile}")
+
+
 def test_vector_kernel_handles_batches_above_16(B):
     M, K, N, group = 37, 512, 136, 128
     case = workloads.make_case(M, K, N, group, seed=5)
