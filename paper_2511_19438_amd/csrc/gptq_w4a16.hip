@@ -116,6 +116,7 @@ Resolved resolve(const Problem &p, const gptq_w4a16_plan_t *plan)
         r.decode.split_k = plan ? plan->split_k : 0;
         decode_make_plan(p, r.decode);
     } else if (kernel == 3) {
+        r.skinny.cols_per_wg = plan ? plan->tile : 0;
         r.skinny.split_k = plan ? plan->split_k : 0;
         skinny_make_plan(p, r.skinny);
     } else {
@@ -220,6 +221,7 @@ int gptq_w4a16_plan_query(int M, int K, int N, int group_size, int act_order, co
         out.tile = r.decode.cols_per_wg;
     } else if (r.kernel == 3) {
         out.split_k = r.skinny.split_k;
+        out.tile = r.skinny.cols_per_wg;
     } else {
         out.split_k = 1;
         out.tile = r.prefill.tile;

@@ -48,6 +48,7 @@ hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspa
 // ---- small batch: MFMA kernel with the vector kernel's split-K decomposition, M <= 64 ----
 constexpr int kSkinnyMaxM = 64;
 struct SkinnyPlan {
+    int cols_per_wg;      // 64 (wavefronts split the K slice) or 256 (wavefronts side by side); 0 = choose
     int split_k;          // number of K slices (0 = choose)
     int units_per_slice;  // 128-k units per slice
 };

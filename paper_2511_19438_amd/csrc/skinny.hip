@@ -19,10 +19,10 @@ int row_blocks(int M)
     return M <= 16 ? 1 : (M <= 32 ? 2 : 4);
 }
 
-template <int TM>
+template <int TM, int WN>
 hipError_t launch_tm(const skinny::Args &a, size_t lds, hipStream_t stream)
 {
-    auto kernel = skinny::skinny_kernel<TM>;
+    auto kernel = skinny::skinny_kernel<TM, WN>;
     if (lds > 48 * 1024) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -45,26 +45,33 @@ void skinny_make_plan(const Problem &p, SkinnyPlan &plan)
 {
     const int rows = 16 * row_blocks(p.M);
     const int total_units = p.K / skinny::kUnitK;
-    const int tiles_n = ceil_div(p.N, skinny::kCols);
     int max_units = kMaxActivationLdsBytes / (rows * 2) / skinny::kUnitK;  // activations of a slice must fit LDS
     if (max_units < 1)
         max_units = 1;
+    if (plan.cols_per_wg != 64 && plan.cols_per_wg != 256) {
+        // Wide tiles stage the activations once for four times as many weights, but a workgroup's wavefronts
+        // then walk the whole slice: that only pays (measured) once the columns alone spread over most of
+        // the chip.
+        plan.cols_per_wg = ceil_div(p.N, 256) >= 192 ? 256 : 64;
+    }
+    const int tiles_n = ceil_div(p.N, plan.cols_per_wg);
+    const int quantum = plan.cols_per_wg == 64 ? 4 : 1;  // narrow tiles: one unit per wavefront and turn
     int ups;
     if (plan.split_k > 0) {
         ups = ceil_div(total_units, plan.split_k < total_units ? plan.split_k : total_units);
     } else {
-        // Whole multiples of four units (one per wavefront), workgroup count as close to 768 as possible - but
-        // the fp32 partial sums that the slices exchange through scratch (8 bytes per slice and output: written
-        // once, read once) may not exceed a quarter of the packed weight bytes (K*N/2), or they, not the
-        // weights, set the time:  split * M * N * 8 <= K * N / 8.
+        // Workgroup count as close to the target as possible - but the fp32 partial sums that the slices
+        // exchange through scratch (8 bytes per slice and output: written once, read once) may not exceed a
+        // quarter of the packed weight bytes (K*N/2), or they, not the weights, set the time:
+        // split * M * N * 8 <= K * N / 8.
         int max_split = p.K / (64 * p.M);
         if (max_split < 1)
             max_split = 1;
         const int min_units = ceil_div(total_units, max_split);
-        const double target = 768.0;
+        const double target = plan.cols_per_wg == 64 ? 768.0 : 512.0;
         ups = 0;
         double best = 0.0;
-        for (int c = 4; c <= total_units + 3; c += 4) {
+        for (int c = quantum; c <= total_units + quantum - 1; c += quantum) {
             const int cand = c < total_units ? c : total_units;
             if (cand > max_units && ups)
                 break;
@@ -111,7 +118,12 @@ hipError_t launch_skinny(const Problem &p, const SkinnyPlan &plan, void *workspa
     a.K = p.K;
     a.N = p.N;
     a.units_per_group = p.group_size / skinny::kUnitK;
-    a.tiles_n = ceil_div(p.N, skinny::kCols);
+    a.unit_group_shift = -1;
+    for (int sh = 0; sh < 20; ++sh)
+        if ((1 << sh) == a.units_per_group)
+            a.unit_group_shift = sh;
+    const int wn = plan.cols_per_wg / skinny::kCols;
+    a.tiles_n = ceil_div(p.N, plan.cols_per_wg);
     a.split_k = plan.split_k;
     a.units_per_slice = plan.units_per_slice;
     a.total_units = p.K / skinny::kUnitK;
@@ -119,12 +131,19 @@ hipError_t launch_skinny(const Problem &p, const SkinnyPlan &plan, void *workspa
     const int tm = row_blocks(p.M);
     const int rows = 16 * tm;
     const size_t xs = (size_t)rows * plan.units_per_slice * skinny::kUnitK * sizeof(half_t);
-    const size_t red = (size_t)skinny::kWaves * rows * skinny::kCols * sizeof(float);
+    const size_t red = (size_t)skinny::kWaves * rows * skinny::kCols * sizeof(float);  // [4/wn][rows][64*wn]
     const size_t lds = xs > red ? xs : red;
+    if (wn == 4) {
+        switch (tm) {
+        case 1: return launch_tm<1, 4>(a, lds, stream);
+        case 2: return launch_tm<2, 4>(a, lds, stream);
+        default: return launch_tm<4, 4>(a, lds, stream);
+        }
+    }
     switch (tm) {
-    case 1: return launch_tm<1>(a, lds, stream);
-    case 2: return launch_tm<2>(a, lds, stream);
-    default: return launch_tm<4>(a, lds, stream);
+    case 1: return launch_tm<1, 1>(a, lds, stream);
+    case 2: return launch_tm<2, 1>(a, lds, stream);
+    default: return launch_tm<4, 1>(a, lds, stream);
     }
 }
 

@@ -21,6 +21,8 @@
 
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace gptq {
 namespace skinny {
 
@@ -39,6 +41,7 @@ struct Args {
     unsigned *counters;  // [tiles_n], zero between launches
     int M, K, N;
     int units_per_group;  // group_size / 128
+    int unit_group_shift; // log2(units_per_group) if that is a power of two, else -1
     int tiles_n;
     int split_k;
     int units_per_slice;  // 128-k units per K slice (multiple of 4 where possible)
@@ -98,10 +101,16 @@ struct UnitRegs {
     uint32_t zb;
 };
 
-template <int TM>  // 16-row blocks: M <= 16 * TM
+// TM: 16-row blocks (M <= 16 * TM).  WN: wavefronts side by side along N (1 or 4).  With WN = 1 the
+// workgroup owns 64 columns and its four wavefronts split the K slice (narrow layers: many small
+// workgroups); with WN = 4 it owns 256 columns, every wavefront walks the whole slice for its own 64
+// columns and the staged activations serve four times as many weights (wide layers).
+template <int TM, int WN>
 __global__ __launch_bounds__(kThreads) void skinny_kernel(const Args a)
 {
     constexpr int ROWS = 16 * TM;
+    constexpr int COLS = kCols * WN;   // columns per workgroup
+    constexpr int KW = kWaves / WN;    // wavefronts that share a column block and split the slice
 
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int s_last;
@@ -114,7 +123,9 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const Args a)
     const int tile = blockIdx.x % a.tiles_n;
     const int slice = blockIdx.x / a.tiles_n;
     const int N = a.N;
-    const int n0 = tile * kCols + 4 * cq;
+    const int cb = wave / KW;  // this wavefront's 64-column block inside the tile
+    const int kw = wave % KW;  // and its share of the slice
+    const int n0 = tile * COLS + cb * kCols + 4 * cq;
     const int nc = min(n0, N - 4);  // clamped for loads; columns past N are never stored
 
     const int u0 = slice * a.units_per_slice;
@@ -124,20 +135,30 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const Args a)
     const int Ls = nunits * kUnitK;  // activations of this slice per row (multiple of 128)
 
     // this wavefront's contiguous share of the slice's units
-    const int per_wave = (nunits + kWaves - 1) / kWaves;
-    const int wu0 = min(u0 + wave * per_wave, u1);
+    const int per_wave = (nunits + KW - 1) / KW;
+    const int wu0 = min(u0 + kw * per_wave, u1);
     const int wu1 = min(wu0 + per_wave, u1);
 
     half_t *xs = reinterpret_cast<half_t *>(smem);  // [ROWS][Ls], 16-byte chunks swizzled by row
 
+    // Addresses are a wavefront-uniform base (the unit, the step and the group are the same for all lanes:
+    // scalar registers) plus a 32-bit byte offset per lane.  Nothing waits on a load where it is issued
+    // (the zero word is shifted when it is used) and no branch sits between a load and its use.
+    const uint32_t voff_w = ((uint32_t)kg * N + nc) * 4u;
+    const uint32_t voff_s = (uint32_t)nc * 2u;
+    const uint32_t voff_z = (uint32_t)(nc >> 3) * 4u;
+    const int zshift = (nc & 4) * 4;
     auto issue = [&](int u, UnitRegs &r) {
-        const int uc = min(u, u1 - 1);  // clamped: loads never branch, a clamped unit is not consumed
+        const int uc = min(u, u1 - 1);  // clamped: a unit past the end is loaded again but not consumed
+        const uint32_t *wrow = a.qweight + (size_t)uc * 16 * N;
 #pragma unroll
         for (int s = 0; s < 4; ++s)
-            r.w[s] = *reinterpret_cast<const uint4 *>(a.qweight + (size_t)(uc * 16 + s * 4 + kg) * N + nc);
-        const int grp = uc / a.units_per_group;
-        r.sc = *reinterpret_cast<const uint2 *>(a.scales + (size_t)grp * N + nc);
-        r.zb = a.qzeros[(size_t)grp * (N >> 3) + (nc >> 3)] >> ((nc & 4) * 4);
+            r.w[s] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(wrow + (size_t)s * 4 * N) +
+                                                      voff_w);
+        const int grp = a.unit_group_shift >= 0 ? (uc >> a.unit_group_shift) : uc / a.units_per_group;
+        r.sc = *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(a.scales + (size_t)grp * N) + voff_s);
+        r.zb = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(a.qzeros + (size_t)grp * (N >> 3)) +
+                                                   voff_z);
     };
 
     UnitRegs ra, rb;
@@ -180,7 +201,7 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const Args a)
         uint32_t nz[4], ss[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const uint32_t z = (r.zb >> (4 * t)) & 15u;
+            const uint32_t z = (r.zb >> (zshift + 4 * t)) & 15u;
             nz[t] = 0xD400E400u | z | (z << 20);
             const uint32_t pair = t < 2 ? r.sc.x : r.sc.y;
             const uint32_t sb = (t & 1) ? (pair >> 16) : (pair & 0xffffu);
@@ -207,47 +228,58 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const Args a)
     };
 
     if (active) {
-        // software pipeline over two register sets: the next unit's weights fly while this one is consumed
+        // Software pipeline over two register sets: the next unit's weights fly while this one is consumed.
+        // The steady-state loop issues unconditionally and the last one or two units are peeled; at a unit
+        // boundary the accumulators are pinned (empty asm) and the scheduler stopped, so that the loads of
+        // the unit after next are issued after this unit's arithmetic: two units in flight, not three.
+        auto unit_boundary = [&]() {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                asm volatile("" : "+v"(acc[i][0]), "+v"(acc[i][1]), "+v"(acc[i][2]), "+v"(acc[i][3])::"memory");
+            __builtin_amdgcn_sched_barrier(0);
+        };
         int u = wu0;
-        while (true) {
-            bool more = u + 1 < wu1;
-            if (more)
-                issue(u + 1, rb);
+        while (u + 2 < wu1) {
+            issue(u + 1, rb);
             consume(u, ra);
-            if (!more)
-                break;
-            ++u;
-            more = u + 1 < wu1;
-            if (more)
-                issue(u + 1, ra);
-            consume(u, rb);
-            if (!more)
-                break;
-            ++u;
+            unit_boundary();
+            issue(u + 2, ra);
+            consume(u + 1, rb);
+            unit_boundary();
+            u += 2;
+        }
+        if (u + 2 == wu1) {
+            issue(u + 1, rb);
+            consume(u, ra);
+            unit_boundary();
+            consume(u + 1, rb);
+        } else {
+            consume(u, ra);
         }
     }
 
-    // ---- reduce over the four wavefronts through LDS (the activation buffer is reused) ----
-    // lane holds, for block i, n-block t, register r: row 16*i + 4*kg + r, column 4*cq + t
+    // ---- through LDS (the activation buffer is reused): reduce over the wavefronts that split the slice
+    //      and turn the MFMA register layout into rows of adjacent columns ----
+    // lane holds, for block i, n-block t, register r: row 16*i + 4*kg + r, column 4*cq + t of its block
     __syncthreads();
-    float *red = reinterpret_cast<float *>(smem);  // [kWaves][ROWS][kCols]
+    float *red = reinterpret_cast<float *>(smem);  // [KW][ROWS][COLS]
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int row = 16 * i + 4 * kg + r;
             float4_t v = {acc[i][0][r], acc[i][1][r], acc[i][2][r], acc[i][3][r]};
-            *reinterpret_cast<float4_t *>(red + ((size_t)wave * ROWS + row) * kCols + 4 * cq) = v;
+            *reinterpret_cast<float4_t *>(red + ((size_t)kw * ROWS + row) * COLS + cb * kCols + 4 * cq) = v;
         }
     __syncthreads();
-    for (int i = tid; i < a.M * kCols; i += kThreads) {
-        const int m = i / kCols;
-        const int col = i - m * kCols;
-        const int n = tile * kCols + col;
-        float s = red[(size_t)m * kCols + col];
+    for (int i = tid; i < a.M * COLS; i += kThreads) {
+        const int m = i / COLS;
+        const int col = i - m * COLS;
+        const int n = tile * COLS + col;
+        float s = red[(size_t)m * COLS + col];
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w)
-            s += red[((size_t)w * ROWS + m) * kCols + col];
+        for (int w = 1; w < KW; ++w)
+            s += red[((size_t)w * ROWS + m) * COLS + col];
         if (n < N) {
             if (a.split_k == 1)
                 a.out[(size_t)m * N + n] = (half_t)s;
@@ -268,25 +300,49 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const Args a)
         }
         __syncthreads();
         if (s_last) {
-            for (int i = tid; i < a.M * kCols; i += kThreads) {
-                const int m = i / kCols;
-                const int n = tile * kCols + (i - m * kCols);
-                if (n < N) {
-                    float s = 0.f;
-                    for (int sl0 = 0; sl0 < a.split_k; sl0 += 8) {
-                        float v[8];
+            // All partial sums a thread needs are requested before the first is used (up to four outputs
+            // times eight slices in flight), so the combine costs one scratch round trip, not one per
+            // output; the additions stay in slice order.
+            auto combine = [&](auto outs) {
+            constexpr int OUTS = decltype(outs)::value;
+            for (int i0 = tid; i0 < a.M * COLS; i0 += OUTS * kThreads) {
+                float s[OUTS];
+                size_t off[OUTS];
+                bool live[OUTS];
+#pragma unroll
+                for (int o = 0; o < OUTS; ++o) {
+                    const int i = min(i0 + o * kThreads, a.M * COLS - 1);
+                    const int m = i / COLS;
+                    const int n = min(tile * COLS + (i - m * COLS), N - 1);
+                    off[o] = (size_t)m * N + n;
+                    live[o] = i0 + o * kThreads < a.M * COLS && tile * COLS + (i - m * COLS) < N;
+                    s[o] = 0.f;
+                }
+                for (int sl0 = 0; sl0 < a.split_k; sl0 += 8) {
+                    float v[OUTS][8];
+#pragma unroll
+                    for (int o = 0; o < OUTS; ++o)
 #pragma unroll
                         for (int j = 0; j < 8; ++j) {
                             const int sl = min(sl0 + j, a.split_k - 1);
-                            v[j] = load_device_scope(a.partial + ((size_t)sl * a.M + m) * N + n);
+                            v[o][j] = load_device_scope(a.partial + (size_t)sl * a.M * N + off[o]);
                         }
 #pragma unroll
+                    for (int o = 0; o < OUTS; ++o)
+#pragma unroll
                         for (int j = 0; j < 8; ++j)
-                            s += (sl0 + j < a.split_k) ? v[j] : 0.f;
-                    }
-                    a.out[(size_t)m * N + n] = (half_t)s;
+                            s[o] += (sl0 + j < a.split_k) ? v[o][j] : 0.f;
                 }
+#pragma unroll
+                for (int o = 0; o < OUTS; ++o)
+                    if (live[o])
+                        a.out[off[o]] = (half_t)s[o];
             }
+            };
+            if (a.M * COLS <= kThreads)
+                combine(std::integral_constant<int, 1>());
+            else
+                combine(std::integral_constant<int, 4>());
             if (tid == 0)
                 __hip_atomic_store(a.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }

@@ -227,23 +227,25 @@ SKINNY_SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("tile", [64, 256])
 @pytest.mark.parametrize("M", [1, 5, 8, 16, 17, 32, 33, 64])
 @pytest.mark.parametrize("K,N,group", SKINNY_SHAPES)
-def test_small_batch_mfma_kernel_matches_oracle(B, M, K, N, group):
+def test_small_batch_mfma_kernel_matches_oracle(B, M, K, N, group, tile):
     case = workloads.make_case(M, K, N, group, seed=3 * K + N + M)
     ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
-    out = run_gemm(B, case, group, B.Plan(kernel=3))
-    assert_within_band(out, ref, f"small-batch M={M} K={K} N={N} g={group}")
+    out = run_gemm(B, case, group, B.Plan(kernel=3, tile=tile))
+    assert_within_band(out, ref, f"small-batch M={M} K={K} N={N} g={group} tile={tile}")
 
 
+@pytest.mark.parametrize("tile", [64, 256])
 @pytest.mark.parametrize("split_k", [1, 2, 3, 5, 16])
 @pytest.mark.parametrize("M", [8, 40])
-def test_small_batch_mfma_kernel_splits(B, split_k, M):
+def test_small_batch_mfma_kernel_splits(B, split_k, M, tile):
     K, N, group = 2048, 776, 128
     case = workloads.make_case(M, K, N, group, seed=177 + M)
     ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
-    out = run_gemm(B, case, group, B.Plan(kernel=3, split_k=split_k))
-    assert_within_band(out, ref, f"small-batch split={split_k} M={M}")
+    out = run_gemm(B, case, group, B.Plan(kernel=3, split_k=split_k, tile=tile))
+    assert_within_band(out, ref, f"small-batch split={split_k} M={M} tile={tile}")
 
 
 def test_small_batch_request_falls_back_when_unsupported(B):
