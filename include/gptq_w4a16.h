@@ -64,9 +64,10 @@ enum gptq_status {
  * dequantise, stage activations on chip, contract, reduce the split-K partial sums on
  * chip and across workgroups, round once to fp16, store).  `out` is OVERWRITTEN and need
  * not be zeroed (unlike the accumulate-by-atomicAdd contract of Eq. 9-10).
- * By default M <= 2 runs the bandwidth-bound split-K vector kernel, 3 <= M <= 32 a small-batch MFMA kernel
- * with the same split-K decomposition (when the format allows: no g_idx, group_size % 128 == 0), larger M
- * the big-tile fp16 MFMA kernel.
+ * By default M = 1 runs the bandwidth-bound split-K vector kernel, 2 <= M <= 32 (up to 64 on layers narrower
+ * than 16384 columns) a small-batch MFMA kernel with the same split-K decomposition (when the format allows:
+ * no g_idx, group_size % 128 == 0; otherwise the vector kernel up to M = 16), larger M the big-tile fp16
+ * MFMA kernel.
  * Accumulation is in fp32; the result differs from the exact sum by fp32 reassociation
  * and the final fp16 rounding only.  The same inputs give bit-identical outputs on every
  * call (no floating point atomics are used).
@@ -81,9 +82,11 @@ GPTQ_API int gptq_w4a16_gemm(const void *x, const void *qweight, const void *qze
  */
 typedef struct gptq_w4a16_plan {
     int kernel;      /* 0 auto, 1 vector split-K kernel (any M, processed 16 rows at a time), 2 big-tile MFMA kernel,
-                        3 small-batch MFMA kernel (M <= 64, no g_idx, group_size % 128 == 0; else falls back) */
-    int split_k;     /* number of K slices (vector kernel); 0 auto */
+                        3 small-batch MFMA kernel (M <= 64, processed 32 rows at a time; no g_idx,
+                        group_size % 128 == 0; else falls back) */
+    int split_k;     /* number of K slices (vector and small-batch kernels); 0 auto */
     int tile;        /* vector kernel: columns per workgroup (16, 32, 64, 128 or 256);
+                        small-batch MFMA kernel: columns per workgroup (64 or 256; anything else = auto);
                         MFMA kernel: tile id 1..10 = rows x columns per workgroup (wavefront grid):
                         1 256x256 (1x4), 2 256x128 (2x2), 3 128x128 (2x2), 4 128x256 (1x4, deep ring),
                         5 64x128 (1x4), 6 32x256 (1x4), 7 256x256 (1x4, 32-k stages), 8 128x256 (1x4),
@@ -101,9 +104,8 @@ GPTQ_API int gptq_w4a16_gemm_plan(const void *x, const void *qweight, const void
  * Host-only: what gptq_w4a16_gemm_plan(..., request) would run for a problem of this shape.
  * `act_order` non-zero means a g_idx array would be passed; `request` may be NULL (automatic).
  * On success *resolved holds the kernel id (1, 2 or 3, never 0), its K split (1 for the big-tile MFMA
- * kernel) and its tile (vector kernel: columns per workgroup; big-tile MFMA kernel: tile id;
- * small-batch MFMA kernel: 0).  Touches no device.  Errors as for gptq_w4a16_gemm_plan's
- * shape and plan checks.
+ * kernel) and its tile (vector and small-batch kernels: columns per workgroup; big-tile MFMA kernel:
+ * tile id).  Touches no device.  Errors as for gptq_w4a16_gemm_plan's shape and plan checks.
  */
 GPTQ_API int gptq_w4a16_plan_query(int M, int K, int N, int group_size, int act_order,
                                    const gptq_w4a16_plan_t *request, gptq_w4a16_plan_t *resolved);

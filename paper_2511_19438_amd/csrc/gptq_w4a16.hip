@@ -79,12 +79,21 @@ int acquire_workspace(size_t bytes, void **out)
     return GPTQ_OK;
 }
 
-// Default kernel by batch size, from measurement on Llama-shaped layers.  Up to 2 rows the vector kernel streams
-// the weights fastest.  From 3 rows it runs out of vector ALU throughput (every weight meets every batch row
-// there) and the small-batch MFMA kernel, whose time is flat up to 16 rows, wins; past 32 rows that kernel's
-// per-workgroup activation staging outgrows its benefit and the big-tile MFMA kernel takes over.
-constexpr int kVectorMaxM = 2;
+// Default kernel by batch size, from measurement on Llama-shaped layers.  A single row is streamed fastest
+// by the vector kernel.  From two rows on the small-batch MFMA kernel wins: its time is nearly flat up to 16
+// rows and grows slowly to 32, where the vector kernel pays for every weight once per batch row.  The
+// big-tile MFMA kernel needs many tiles to fill the chip; up to 64 rows the small-batch kernel (two launches
+// of 32 rows) is still ahead of it unless the layer is very wide.
+constexpr int kVectorMaxM = 1;
 constexpr int kSmallBatchAutoMaxM = 32;
+constexpr int kSmallBatchTwoLaunchMaxN = 16384;
+
+bool small_batch_by_default(const Problem &p)
+{
+    if (!skinny_supported(p))
+        return false;
+    return p.M <= kSmallBatchAutoMaxM || (p.M <= kSkinnyMaxM && p.N < kSmallBatchTwoLaunchMaxN);
+}
 
 // What a call resolves to: the kernel and its decomposition, after the automatic choices.
 struct Resolved {
@@ -101,7 +110,7 @@ Resolved resolve(const Problem &p, const gptq_w4a16_plan_t *plan)
     if (kernel == 0) {
         if (p.M <= kVectorMaxM)
             kernel = 1;
-        else if (p.M <= kSmallBatchAutoMaxM && skinny_supported(p))
+        else if (small_batch_by_default(p))
             kernel = 3;
         else
             kernel = (p.M <= kDecodeMaxM) ? 1 : 2;

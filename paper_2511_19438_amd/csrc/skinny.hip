@@ -14,9 +14,18 @@ int ceil_div(int a, int b)
     return (a + b - 1) / b;
 }
 
+// Batches of more than 32 rows are processed 32 rows at a time (one launch each, same stream): the weights
+// are streamed once per launch, the second time mostly from the memory-side cache.
+constexpr int kRowsPerLaunch = 32;
+
 int row_blocks(int M)
 {
-    return M <= 16 ? 1 : (M <= 32 ? 2 : 4);
+    return M <= 16 ? 1 : 2;
+}
+
+int rows_of_launch(int M)
+{
+    return M < kRowsPerLaunch ? M : kRowsPerLaunch;
 }
 
 template <int TM, int WN>
@@ -43,49 +52,42 @@ bool skinny_supported(const Problem &p)
 
 void skinny_make_plan(const Problem &p, SkinnyPlan &plan)
 {
-    const int rows = 16 * row_blocks(p.M);
+    const int launch_m = rows_of_launch(p.M);
+    const int rows = 16 * row_blocks(launch_m);
     const int total_units = p.K / skinny::kUnitK;
-    int max_units = kMaxActivationLdsBytes / (rows * 2) / skinny::kUnitK;  // activations of a slice must fit LDS
-    if (max_units < 1)
-        max_units = 1;
     if (plan.cols_per_wg != 64 && plan.cols_per_wg != 256) {
         // Wide tiles stage the activations once for four times as many weights, but a workgroup's wavefronts
         // then walk the whole slice: that only pays (measured) once the columns alone spread over most of
         // the chip.
         plan.cols_per_wg = ceil_div(p.N, 256) >= 192 ? 256 : 64;
     }
+    // where the activations of a slice are staged in LDS (wide tiles, more than 32 rows) they must fit
+    const bool direct = plan.cols_per_wg == 64;
+    int max_units = direct ? total_units : kMaxActivationLdsBytes / (rows * 2 + 8) / skinny::kUnitK;
+    if (max_units < 1)
+        max_units = 1;
     const int tiles_n = ceil_div(p.N, plan.cols_per_wg);
     const int quantum = plan.cols_per_wg == 64 ? 4 : 1;  // narrow tiles: one unit per wavefront and turn
     int ups;
     if (plan.split_k > 0) {
         ups = ceil_div(total_units, plan.split_k < total_units ? plan.split_k : total_units);
     } else {
-        // Workgroup count as close to the target as possible - but the fp32 partial sums that the slices
-        // exchange through scratch (8 bytes per slice and output: written once, read once) may not exceed a
-        // quarter of the packed weight bytes (K*N/2), or they, not the weights, set the time:
-        // split * M * N * 8 <= K * N / 8.
-        int max_split = p.K / (64 * p.M);
+        // One workgroup per compute unit is the target (measured: 192..344 unsplit workgroups beat any split
+        // of the same layer, and narrow layers want tiles * split = 256) - but the fp32 partial sums that the
+        // slices exchange through scratch (8 bytes per slice and output: written once, read once) may not
+        // exceed a quarter of the packed weight bytes (K*N/2), or they, not the weights, set the time:
+        // split * M * N * 8 <= K * N / 8.  Slices are whole multiples of `quantum` units.
+        int max_split = p.K / (64 * launch_m);
         if (max_split < 1)
             max_split = 1;
-        const int min_units = ceil_div(total_units, max_split);
-        const double target = plan.cols_per_wg == 64 ? 768.0 : 512.0;
-        ups = 0;
-        double best = 0.0;
-        for (int c = quantum; c <= total_units + quantum - 1; c += quantum) {
-            const int cand = c < total_units ? c : total_units;
-            if (cand > max_units && ups)
-                break;
-            if (cand < min_units && cand < max_units && cand < total_units)
-                continue;
-            const double wgs = (double)tiles_n * ceil_div(total_units, cand);
-            const double ratio = wgs > target ? wgs / target : target / wgs;
-            if (!ups || ratio < best - 1e-9) {
-                ups = cand;
-                best = ratio;
-            }
-            if (cand == total_units)
-                break;
-        }
+        int split = (256 + tiles_n / 2) / tiles_n;
+        if (split > max_split)
+            split = max_split;
+        if (split < 1)
+            split = 1;
+        ups = ceil_div(ceil_div(total_units, split), quantum) * quantum;
+        if (ups > total_units)
+            ups = total_units;
     }
     if (ups > max_units)
         ups = max_units;
@@ -99,52 +101,54 @@ size_t skinny_workspace_bytes(const Problem &p, const SkinnyPlan &plan)
 {
     size_t bytes = kCounterBytes;
     if (plan.split_k > 1)
-        bytes += (size_t)plan.split_k * p.M * p.N * sizeof(float);
+        bytes += (size_t)plan.split_k * rows_of_launch(p.M) * p.N * sizeof(float);
     return bytes;
 }
 
 hipError_t launch_skinny(const Problem &p, const SkinnyPlan &plan, void *workspace, hipStream_t stream)
 {
     unsigned char *ws = static_cast<unsigned char *>(workspace);
-    skinny::Args a;
-    a.x = p.x;
-    a.qweight = p.qweight;
-    a.qzeros = p.qzeros;
-    a.scales = p.scales;
-    a.out = p.out;
-    a.counters = reinterpret_cast<unsigned *>(ws);
-    a.partial = reinterpret_cast<float *>(ws + kCounterBytes);
-    a.M = p.M;
-    a.K = p.K;
-    a.N = p.N;
-    a.units_per_group = p.group_size / skinny::kUnitK;
-    a.unit_group_shift = -1;
-    for (int sh = 0; sh < 20; ++sh)
-        if ((1 << sh) == a.units_per_group)
-            a.unit_group_shift = sh;
     const int wn = plan.cols_per_wg / skinny::kCols;
-    a.tiles_n = ceil_div(p.N, plan.cols_per_wg);
-    a.split_k = plan.split_k;
-    a.units_per_slice = plan.units_per_slice;
-    a.total_units = p.K / skinny::kUnitK;
+    for (int m0 = 0; m0 < p.M; m0 += kRowsPerLaunch) {
+        skinny::Args a;
+        a.x = p.x + (size_t)m0 * p.K;
+        a.qweight = p.qweight;
+        a.qzeros = p.qzeros;
+        a.scales = p.scales;
+        a.out = p.out + (size_t)m0 * p.N;
+        a.counters = reinterpret_cast<unsigned *>(ws);
+        a.partial = reinterpret_cast<float *>(ws + kCounterBytes);
+        a.M = (p.M - m0) < kRowsPerLaunch ? (p.M - m0) : kRowsPerLaunch;
+        a.K = p.K;
+        a.N = p.N;
+        a.units_per_group = p.group_size / skinny::kUnitK;
+        a.unit_group_shift = -1;
+        for (int sh = 0; sh < 20; ++sh)
+            if ((1 << sh) == a.units_per_group)
+                a.unit_group_shift = sh;
+        a.tiles_n = ceil_div(p.N, plan.cols_per_wg);
+        a.split_k = plan.split_k;
+        a.units_per_slice = plan.units_per_slice;
+        a.total_units = p.K / skinny::kUnitK;
 
-    const int tm = row_blocks(p.M);
-    const int rows = 16 * tm;
-    const size_t xs = (size_t)rows * plan.units_per_slice * skinny::kUnitK * sizeof(half_t);
-    const size_t red = (size_t)skinny::kWaves * rows * skinny::kCols * sizeof(float);  // [4/wn][rows][64*wn]
-    const size_t lds = xs > red ? xs : red;
-    if (wn == 4) {
-        switch (tm) {
-        case 1: return launch_tm<1, 4>(a, lds, stream);
-        case 2: return launch_tm<2, 4>(a, lds, stream);
-        default: return launch_tm<4, 4>(a, lds, stream);
-        }
+        const int tm = row_blocks(a.M);
+        const int rows = 16 * tm;
+        // 64-column workgroups read the activations straight from global memory
+        const bool direct = wn == 1;
+        const size_t xs = direct ? 0
+                                 : (size_t)rows * plan.units_per_slice * skinny::kUnitK * sizeof(half_t)  // activations
+                                       + (size_t)rows * plan.units_per_slice * 8;                        // and their sums
+        const size_t red = (size_t)skinny::kWaves * rows * skinny::kCols * sizeof(float);  // [4/wn][rows][64*wn]
+        const size_t lds = xs > red ? xs : red;
+        hipError_t err;
+        if (wn == 4)
+            err = tm == 1 ? launch_tm<1, 4>(a, lds, stream) : launch_tm<2, 4>(a, lds, stream);
+        else
+            err = tm == 1 ? launch_tm<1, 1>(a, lds, stream) : launch_tm<2, 1>(a, lds, stream);
+        if (err != hipSuccess)
+            return err;
     }
-    switch (tm) {
-    case 1: return launch_tm<1, 1>(a, lds, stream);
-    case 2: return launch_tm<2, 1>(a, lds, stream);
-    default: return launch_tm<4, 1>(a, lds, stream);
-    }
+    return hipSuccess;
 }
 
 }  // namespace gptq

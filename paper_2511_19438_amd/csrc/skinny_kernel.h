@@ -55,35 +55,21 @@ __device__ __forceinline__ half2_t as_half2(uint32_t v)
     return __builtin_bit_cast(half2_t, v);
 }
 
-struct PairMagic {
-    uint32_t mask, bias;
-    __device__ __forceinline__ PairMagic()
+// Bit patterns that turn 4-bit codes into fp16 values without an integer-to-float conversion:
+// 0x6400 is 1024.0 (ulp 1): OR-ing a nibble into bits 0..3 gives 1024 + q exactly;
+// 0x5400 is 64.0 (ulp 1/16): OR-ing a nibble into bits 4..7 gives 64 + q exactly.
+// The constants are kept in registers (not literals) so that each pair costs ONE v_and_or_b32.
+struct NibbleMagic {
+    uint32_t mask_lo, mask_hi, bias_lo, bias_hi;
+    __device__ __forceinline__ NibbleMagic()
     {
-        mask = 0x00f0000fu;  // one nibble per half
-        bias = 0x54006400u;  // (64.0 with ulp 1/16, 1024.0 with ulp 1)
-        asm volatile("" : "+s"(mask), "+v"(bias));
+        mask_lo = 0x000f000fu;
+        mask_hi = 0x00f000f0u;
+        bias_lo = 0x64006400u;
+        bias_hi = 0x54005400u;
+        asm volatile("" : "+s"(mask_lo), "+s"(mask_hi), "+v"(bias_lo), "+v"(bias_hi));
     }
 };
-
-// Pair P (k = 2P, 2P+1) of a packed word -> the bits of (s*(q_2P - z), s*(q_2P+1 - z)); see the MFMA
-// prefill kernel for the bit trick.  nz = (-(1024+z), -(64+z)), ss = (s, s).
-template <int P>
-__device__ __forceinline__ uint32_t dequant_pair(uint32_t w, const PairMagic &k, uint32_t nz, uint32_t ss)
-{
-    const uint32_t spread = __builtin_amdgcn_perm(0u, w, 0x0c000c00u | P | (P << 16));
-    const half2_t v = (as_half2((spread & k.mask) | k.bias) + as_half2(nz)) * as_half2(ss);
-    return __builtin_bit_cast(uint32_t, v);
-}
-
-__device__ __forceinline__ half8_t dequant_word(uint32_t w, const PairMagic &k, uint32_t nz, uint32_t ss)
-{
-    u32x4_t r;
-    r[0] = dequant_pair<0>(w, k, nz, ss);
-    r[1] = dequant_pair<1>(w, k, nz, ss);
-    r[2] = dequant_pair<2>(w, k, nz, ss);
-    r[3] = dequant_pair<3>(w, k, nz, ss);
-    return __builtin_bit_cast(half8_t, r);
-}
 
 __device__ __forceinline__ void store_device_scope(float *p, float v)
 {
@@ -95,10 +81,12 @@ __device__ __forceinline__ float load_device_scope(const float *p)
 }
 
 // Loads of one 128-k unit of one lane: 4 steps x 4 adjacent words, plus the unit's scales and zero word.
+template <int XROWS>  // XROWS: 16-row blocks of activations that travel with the weights (0: they are in LDS)
 struct UnitRegs {
     uint4 w[4];
     uint2 sc;  // four fp16 scales as raw bits
     uint32_t zb;
+    u32x4_t xa[XROWS > 0 ? XROWS : 1][4];  // A operand per row block and k step
 };
 
 // TM: 16-row blocks (M <= 16 * TM).  WN: wavefronts side by side along N (1 or 4).  With WN = 1 the
@@ -111,6 +99,12 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const Args a)
     constexpr int ROWS = 16 * TM;
     constexpr int COLS = kCols * WN;   // columns per workgroup
     constexpr int KW = kWaves / WN;    // wavefronts that share a column block and split the slice
+    // With 64-column workgroups every activation is used by exactly one lane (the wavefronts split the
+    // slice), so staging them in LDS would be a copy without reuse: each lane loads its A operand straight
+    // from global memory (L2), in the same pipeline as the weights.  With 256-column workgroups the four
+    // wavefronts share the slice and the activations are staged once in LDS.
+    constexpr bool DIRECT = WN == 1;
+    using Regs = UnitRegs<DIRECT ? TM : 0>;
 
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int s_last;
@@ -148,7 +142,11 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const Args a)
     const uint32_t voff_s = (uint32_t)nc * 2u;
     const uint32_t voff_z = (uint32_t)(nc >> 3) * 4u;
     const int zshift = (nc & 4) * 4;
-    auto issue = [&](int u, UnitRegs &r) {
+    uint32_t voff_x[TM];  // DIRECT: this lane's row and k group inside a 32-k step, as a byte offset
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+        voff_x[i] = ((uint32_t)min(16 * i + cq, a.M - 1) * a.K + kg * 8) * 2u;
+    auto issue = [&](int u, Regs &r) {
         const int uc = min(u, u1 - 1);  // clamped: a unit past the end is loaded again but not consumed
         const uint32_t *wrow = a.qweight + (size_t)uc * 16 * N;
 #pragma unroll
@@ -159,18 +157,27 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const Args a)
         r.sc = *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(a.scales + (size_t)grp * N) + voff_s);
         r.zb = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(a.qzeros + (size_t)grp * (N >> 3)) +
                                                    voff_z);
+        if (DIRECT) {
+            const half_t *xrow = a.x + (size_t)uc * kUnitK;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int st = 0; st < 4; ++st)
+                    r.xa[i][st] = *reinterpret_cast<const u32x4_t *>(reinterpret_cast<const char *>(xrow + st * 32) +
+                                                                     voff_x[i]);
+        }
     };
 
-    UnitRegs ra, rb;
+    Regs ra, rb;
     const bool active = wu0 < wu1;
     if (active)
-        issue(wu0, ra);  // weights are in flight while the activations are staged
+        issue(wu0, ra);  // in flight while the activations are staged (when they are)
 
     // ---- stage the activations global -> LDS by DMA (no registers, all loads in flight at once): 16-byte slot p
     //      of the buffer holds, for row m = p / chunks, the chunk whose index is p % chunks with its low four
     //      bits XORed with m (the swizzle is its own inverse).  Rows past M repeat row M-1: their outputs are
     //      never stored.
-    {
+    if (!DIRECT) {
         typedef __attribute__((address_space(3))) void lds_ptr_t;
         typedef __attribute__((address_space(1))) const void global_ptr_t;
         const int chunks = Ls >> 3;
@@ -185,8 +192,42 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const Args a)
                                              (lds_ptr_t *)(smem + (size_t)(j * kThreads + wave * 64) * 16), 16, 0, 0);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the DMA is not ordered against LDS reads by the compiler
+        __syncthreads();
     }
-    __syncthreads();
+
+    // ---- per (unit, row): S = sum of the unit's 128 activations and S_odd = the sum over odd k, by MFMA
+    //      against a constant operand (column 0: ones, column 1: ones at odd k), each split into an fp16
+    //      high and low part (22 significant bits) and kept in LDS as four halves
+    //      [S_hi, S_lo, S_odd_hi, S_odd_lo] for the correction step of the main loop ----
+    uint2 *xc = reinterpret_cast<uint2 *>(smem + (size_t)ROWS * Ls * sizeof(half_t));  // [nunits][ROWS]
+    if (!DIRECT) {
+        const uint32_t ones = cq == 0 ? 0x3C003C00u : (cq == 1 ? 0x3C000000u : 0u);
+        const half8_t bsum = __builtin_bit_cast(half8_t, u32x4_t{ones, ones, ones, ones});
+        for (int idx = wave; idx < nunits * TM; idx += kWaves) {
+            const int j = idx / TM;
+            const int i = idx - j * TM;
+            const int m = 16 * i + cq;
+            float4_t d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                const int c = (j * 4 + st) * 4 + kg;
+                const int pc = (c & ~15) | ((c ^ m) & 15);
+                const half8_t av = *reinterpret_cast<const half8_t *>(xs + (size_t)m * Ls + pc * 8);
+                d = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bsum, d, 0, 0, 0);
+            }
+            if (cq < 2) {
+                uint32_t *dst = reinterpret_cast<uint32_t *>(xc + (size_t)j * ROWS + 16 * i + 4 * kg) + cq;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const half_t hi = (half_t)d[r];
+                    const half_t lo = (half_t)(d[r] - (float)hi);
+                    dst[2 * r] = (uint32_t)__builtin_bit_cast(uint16_t, hi) |
+                                 ((uint32_t)__builtin_bit_cast(uint16_t, lo) << 16);
+                }
+            }
+        }
+        __syncthreads();
+    }
 
     float4_t acc[TM][4];
 #pragma unroll
@@ -195,34 +236,106 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const Args a)
         for (int t = 0; t < 4; ++t)
             acc[i][t] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-    const PairMagic magic;
+    const NibbleMagic magic;
 
-    auto consume = [&](int u, const UnitRegs &r) {
-        uint32_t nz[4], ss[4];
+    // One unit: 128 k of this lane's four columns against all batch rows.
+    //
+    // The B operand is the biased code, not the weight: a pair of nibbles four k apart is masked out of the
+    // packed word and OR-ed into the mantissa of 1024.0 (even k) or 64.0 (odd k), five vector operations
+    // per packed word instead of sixteen for exact per-element weights.  The MFMA chain of the unit then
+    // holds sum_k x_k (bias_k + q_k); one more MFMA per n-block subtracts sum_k x_k (bias_k + z), written as
+    // (1024 + z) S - 960 S_odd with the staged sums as A operand, and the group's scale is applied to the
+    // chain's result in fp32:  acc += s * sum_k x_k (q_k - z).
+    // DIRECT: constant B operand of the sums, in the operand's k order (0,4) (1,5) (2,6) (3,7):
+    // column 0 adds all k, column 1 the odd ones
+    const uint32_t ones_even = cq == 0 ? 0x3C003C00u : 0u;
+    const uint32_t ones_odd = cq <= 1 ? 0x3C003C00u : 0u;
+    const half8_t bsum = __builtin_bit_cast(half8_t, u32x4_t{ones_even, ones_odd, ones_even, ones_odd});
+
+    auto consume = [&](int u, const Regs &r) {
+        const int j = u - u0;
+        uint32_t cz[4];
+        float sf[4], zf[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const uint32_t z = (r.zb >> (zshift + 4 * t)) & 15u;
-            nz[t] = 0xD400E400u | z | (z << 20);
+            cz[t] = 0xE400E400u | (z * 0x00010001u);  // (-(1024 + z), -(1024 + z))
+            zf[t] = -1024.f - (float)z;
             const uint32_t pair = t < 2 ? r.sc.x : r.sc.y;
-            const uint32_t sb = (t & 1) ? (pair >> 16) : (pair & 0xffffu);
-            ss[t] = sb | (sb << 16);
+            const uint16_t sb = (uint16_t)((t & 1) ? (pair >> 16) : (pair & 0xffffu));
+            sf[t] = (float)__builtin_bit_cast(half_t, sb);
         }
+        float4_t d[TM][4];
+        float4_t dsum[TM];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const uint32_t w[4] = {r.w[s].x, r.w[s].y, r.w[s].z, r.w[s].w};
+        for (int st = 0; st < 4; ++st) {
+            const uint32_t w[4] = {r.w[st].x, r.w[st].y, r.w[st].z, r.w[st].w};
             half8_t b[4];
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
-                b[t] = dequant_word(w[t], magic, nz[t], ss[t]);
-            const int c = ((u - u0) * 4 + s) * 4 + kg;  // 16-byte chunk of the activation row
+            for (int t = 0; t < 4; ++t) {
+                const uint32_t w8 = w[t] >> 8;
+                // k order inside the operand: (0,4) (1,5) (2,6) (3,7)
+                const u32x4_t codes = {(w[t] & magic.mask_lo) | magic.bias_lo, (w[t] & magic.mask_hi) | magic.bias_hi,
+                                       (w8 & magic.mask_lo) | magic.bias_lo, (w8 & magic.mask_hi) | magic.bias_hi};
+                b[t] = __builtin_bit_cast(half8_t, codes);
+            }
+            const int c = (j * 4 + st) * 4 + kg;  // 16-byte chunk of the activation row
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                const int m = 16 * i + cq;  // the A operand lane holds row lane % 16
-                const int pc = (c & ~15) | ((c ^ m) & 15);
-                const half8_t av = *reinterpret_cast<const half8_t *>(xs + (size_t)m * Ls + pc * 8);
+                u32x4_t xv;
+                if (DIRECT) {
+                    xv = r.xa[i][st];
+                } else {
+                    const int m = 16 * i + cq;  // the A operand lane holds row lane % 16
+                    const int pc = (c & ~15) | ((c ^ m) & 15);
+                    xv = *reinterpret_cast<const u32x4_t *>(xs + (size_t)m * Ls + pc * 8);
+                }
+                // the same k order for the activations: halves (0,4) (1,5) (2,6) (3,7)
+                const u32x4_t xp = {__builtin_amdgcn_perm(xv[2], xv[0], 0x05040100u),
+                                    __builtin_amdgcn_perm(xv[2], xv[0], 0x07060302u),
+                                    __builtin_amdgcn_perm(xv[3], xv[1], 0x05040100u),
+                                    __builtin_amdgcn_perm(xv[3], xv[1], 0x07060302u)};
+                const half8_t av = __builtin_bit_cast(half8_t, xp);
+                const float4_t zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
-                    acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b[t], acc[i][t], 0, 0, 0);
+                    d[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b[t], st == 0 ? zero : d[i][t], 0, 0, 0);
+                if (DIRECT)
+                    dsum[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bsum, st == 0 ? zero : dsum[i], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            if (DIRECT) {
+                // S and S_odd of row 4*kg + r sit in lanes 0 and 1 of this lane's row of sixteen: broadcast them
+                // (DPP row_share) and take the bias and the zero point off in fp32
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const float sums = dsum[i][rr];  // (a bit_cast applied to the subscript itself reads element 0)
+                    const int bits = __float_as_int(sums);
+                    const float S = __int_as_float(__builtin_amdgcn_update_dpp(0, bits, 0x150, 0xf, 0xf, false));
+                    const float So = __int_as_float(__builtin_amdgcn_update_dpp(0, bits, 0x151, 0xf, 0xf, false));
+                    const float so960 = 960.f * So;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const float v = __builtin_fmaf(zf[t], S, d[i][t][rr]) + so960;  // sum_k x_k (q_k - z)
+                        acc[i][t][rr] = __builtin_fmaf(sf[t], v, acc[i][t][rr]);
+                    }
+                }
+            } else {
+                uint2 sums = xc[(size_t)j * ROWS + 16 * i + cq];
+                if (kg != 0)
+                    sums = make_uint2(0u, 0u);  // the correction occupies the first four k slots only
+                const half8_t av = __builtin_bit_cast(half8_t, u32x4_t{sums.x, sums.y, 0u, 0u});
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const half8_t bv =
+                        __builtin_bit_cast(half8_t, u32x4_t{cz[t], 0x63806380u /* (960, 960) */, 0u, 0u});
+                    d[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, d[i][t], 0, 0, 0);
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr)
+                        acc[i][t][rr] = __builtin_fmaf(sf[t], d[i][t][rr], acc[i][t][rr]);
+                }
             }
         }
     };
