@@ -101,6 +101,31 @@ GPTQ_API int gptq_w4a16_gemm_plan(const void *x, const void *qweight, const void
                          gptq_stream_t stream, const gptq_w4a16_plan_t *plan);
 
 /*
+ * One-time repack of an act-order checkpoint (Section 2.1: with activation ordering, row k of the
+ * weight belongs to group g_idx[k]; the map is fixed once the checkpoint is loaded).
+ * Writes perm int32[K] (device) = the stable order of k by g_idx[k], and qweight_sorted int32[K/8, N]
+ * (device, same packing as qweight, must not alias it) whose row j is row perm[j] of qweight, so that
+ * row j belongs to group j / group_size like a checkpoint without g_idx.  qzeros and scales are used
+ * unchanged afterwards.  Requires every group to own exactly group_size rows (what the quantiser
+ * produces): otherwise GPTQ_UNSUPPORTED_SHAPE; an entry of g_idx outside [0, K/group_size) gives
+ * GPTQ_INVALID_ARG; in both cases the outputs are undefined.  Blocks until the work on `stream` is
+ * done (it reads a status word back) and allocates a few bytes of device memory meanwhile.
+ */
+GPTQ_API int gptq_w4a16_act_order_prepare(const void *qweight, const void *g_idx, void *qweight_sorted, void *perm,
+                                          int K, int N, int group_size, gptq_stream_t stream);
+
+/*
+ * The act-order GEMM on a repacked checkpoint:  out[m, n] = sum_j x[m, perm[j]] * W_sorted[j, n],
+ * equal (up to the order of the fp32 additions) to gptq_w4a16_gemm with the original qweight and
+ * g_idx.  x is gathered into scratch (M*K fp16) and the kernels of the plain format run on it;
+ * otherwise the contract of gptq_w4a16_gemm.  A caller-owned workspace must hold
+ * gptq_w4a16_workspace_bytes(M, K, N, group_size) + 256 + 2*M*K bytes.
+ */
+GPTQ_API int gptq_w4a16_gemm_prepared(const void *x, const void *qweight_sorted, const void *qzeros,
+                                      const void *scales, const void *perm, void *out, int M, int K, int N,
+                                      int group_size, gptq_stream_t stream);
+
+/*
  * Host-only: what gptq_w4a16_gemm_plan(..., request) would run for a problem of this shape.
  * `act_order` non-zero means a g_idx array would be passed; `request` may be NULL (automatic).
  * On success *resolved holds the kernel id (1, 2 or 3, never 0), its K split (1 for the big-tile MFMA

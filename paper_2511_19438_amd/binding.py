@@ -33,7 +33,8 @@ class Plan(ctypes.Structure):
                 ("flags", ctypes.c_int), ("reserved", ctypes.c_int * 4)]
 
 
-EXPORTS = ("gptq_w4a16_gemm", "gptq_w4a16_gemm_plan", "gptq_w4a16_plan_query", "gptq_w4a16_dequant", "gptq_w4a16_unpack",
+EXPORTS = ("gptq_w4a16_gemm", "gptq_w4a16_gemm_plan", "gptq_w4a16_plan_query", "gptq_w4a16_act_order_prepare",
+           "gptq_w4a16_gemm_prepared", "gptq_w4a16_dequant", "gptq_w4a16_unpack",
            "gptq_w4a16_workspace_bytes", "gptq_w4a16_set_workspace", "gptq_w4a16_strerror", "gptq_w4a16_version")
 
 
@@ -54,6 +55,10 @@ def load() -> ctypes.CDLL:
     lib.gptq_w4a16_gemm_plan.restype = ci
     lib.gptq_w4a16_plan_query.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(Plan), ctypes.POINTER(Plan)]
     lib.gptq_w4a16_plan_query.restype = ci
+    lib.gptq_w4a16_act_order_prepare.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp]
+    lib.gptq_w4a16_act_order_prepare.restype = ci
+    lib.gptq_w4a16_gemm_prepared.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, vp]
+    lib.gptq_w4a16_gemm_prepared.restype = ci
     lib.gptq_w4a16_dequant.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, vp]
     lib.gptq_w4a16_dequant.restype = ci
     lib.gptq_w4a16_unpack.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp]
@@ -127,6 +132,38 @@ def gptq_w4a16_gemm(x, qweight, qzeros, scales, g_idx, out, group_size: int, pla
         rc = lib.gptq_w4a16_gemm_plan(*args, ctypes.byref(plan))
     if rc != 0:
         raise GptqError(rc, "gptq_w4a16_gemm")
+    return out
+
+
+def gptq_w4a16_act_order_prepare(qweight, g_idx, qweight_sorted, perm, group_size: int):
+    """One-time repack of an act-order checkpoint: fills perm[K] (int32) and qweight_sorted[K/8, N] (int32).  Blocks."""
+    K, N = qweight.shape[0] * 8, qweight.shape[1]
+    if tuple(g_idx.shape) != (K,) or tuple(perm.shape) != (K,):
+        raise ValueError(f"g_idx and perm must be [{K}]")
+    if tuple(qweight_sorted.shape) != tuple(qweight.shape):
+        raise ValueError("qweight_sorted must have the shape of qweight")
+    rc = load().gptq_w4a16_act_order_prepare(_ptr(qweight, torch.int32, "qweight"), _ptr(g_idx, torch.int32, "g_idx"),
+                                             _ptr(qweight_sorted, torch.int32, "qweight_sorted"),
+                                             _ptr(perm, torch.int32, "perm"), K, N, int(group_size), _stream())
+    if rc != 0:
+        raise GptqError(rc, "gptq_w4a16_act_order_prepare")
+    return qweight_sorted, perm
+
+
+def gptq_w4a16_gemm_prepared(x, qweight_sorted, qzeros, scales, perm, out, group_size: int):
+    """The act-order GEMM on a repacked checkpoint: out = x[:, perm] @ W_sorted."""
+    K, N = _shapes(qweight_sorted, qzeros, scales, perm, group_size)
+    if x.dim() != 2 or x.shape[1] != K:
+        raise ValueError(f"x must be [M, {K}], got {tuple(x.shape)}")
+    M = x.shape[0]
+    if tuple(out.shape) != (M, N):
+        raise ValueError(f"out must be [{M}, {N}], got {tuple(out.shape)}")
+    rc = load().gptq_w4a16_gemm_prepared(
+        _ptr(x, torch.float16, "x"), _ptr(qweight_sorted, torch.int32, "qweight_sorted"),
+        _ptr(qzeros, torch.int32, "qzeros"), _ptr(scales, torch.float16, "scales"), _ptr(perm, torch.int32, "perm"),
+        _ptr(out, torch.float16, "out"), M, K, N, int(group_size), _stream())
+    if rc != 0:
+        raise GptqError(rc, "gptq_w4a16_gemm_prepared")
     return out
 
 

@@ -37,7 +37,8 @@ def units():
            ("unpack_dequant.hip", "unpack_dequant.o", []),
            ("decode.hip", "decode.o", []),
            ("prefill.hip", "prefill.o", []),
-           ("skinny.hip", "skinny.o", [])]
+           ("skinny.hip", "skinny.o", []),
+           ("act_order.hip", "act_order.o", [])]
     for mb in DECODE_BATCHES:
         out.append(("decode_mb.hip", f"decode_mb{mb}.o", [f"-DGPTQ_DECODE_MB={mb}"]))
     for t in PREFILL_TILES:

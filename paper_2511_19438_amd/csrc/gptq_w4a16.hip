@@ -135,24 +135,42 @@ Resolved resolve(const Problem &p, const gptq_w4a16_plan_t *plan)
     return r;
 }
 
+size_t scratch_bytes(const Problem &p, const Resolved &r)
+{
+    if (r.kernel == 1)
+        return decode_workspace_bytes(p, r.decode);
+    if (r.kernel == 3)
+        return skinny_workspace_bytes(p, r.skinny);
+    return decode_counter_bytes(p.N);  // the big-tile MFMA kernel uses none; keep the counter area valid
+}
+
+int launch_resolved(const Problem &p, const Resolved &r, void *ws, hipStream_t stream)
+{
+    hipError_t err;
+    if (r.kernel == 1)
+        err = launch_decode(p, r.decode, ws, stream);
+    else if (r.kernel == 3)
+        err = launch_skinny(p, r.skinny, ws, stream);
+    else
+        err = launch_prefill(p, r.prefill, stream);
+    return err == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
+}
+
 int run_gemm(const Problem &p, hipStream_t stream, const gptq_w4a16_plan_t *plan)
 {
     const Resolved r = resolve(p, plan);
-    if (r.kernel == 1) {
-        void *ws = nullptr;
-        const int rc = acquire_workspace(decode_workspace_bytes(p, r.decode), &ws);
+    void *ws = nullptr;
+    if (r.kernel != 2) {
+        const int rc = acquire_workspace(scratch_bytes(p, r), &ws);
         if (rc != GPTQ_OK)
             return rc;
-        return launch_decode(p, r.decode, ws, stream) == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
     }
-    if (r.kernel == 3) {
-        void *ws = nullptr;
-        const int rc = acquire_workspace(skinny_workspace_bytes(p, r.skinny), &ws);
-        if (rc != GPTQ_OK)
-            return rc;
-        return launch_skinny(p, r.skinny, ws, stream) == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
-    }
-    return launch_prefill(p, r.prefill, stream) == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
+    return launch_resolved(p, r, ws, stream);
+}
+
+size_t align256(size_t v)
+{
+    return (v + 255) & ~(size_t)255;
 }
 
 int check_plan(const gptq_w4a16_plan_t *plan)
@@ -237,6 +255,80 @@ int gptq_w4a16_plan_query(int M, int K, int N, int group_size, int act_order, co
     }
     *resolved = out;
     return GPTQ_OK;
+}
+
+int gptq_w4a16_act_order_prepare(const void *qweight, const void *g_idx, void *qweight_sorted, void *perm, int K,
+                                 int N, int group_size, gptq_stream_t stream)
+{
+    if (!qweight || !g_idx || !qweight_sorted || !perm)
+        return GPTQ_INVALID_ARG;
+    const int rc = check_shape(K, N, group_size);
+    if (rc != GPTQ_OK)
+        return rc;
+    if (!aligned16(qweight) || !aligned16(g_idx) || !aligned16(qweight_sorted) || !aligned16(perm))
+        return GPTQ_MISALIGNED;
+    if (qweight == qweight_sorted)
+        return GPTQ_INVALID_ARG;  // the gather is not in place
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int *status = nullptr;
+    if (hipMalloc(reinterpret_cast<void **>(&status), sizeof(int)) != hipSuccess)
+        return GPTQ_HIP_ERROR;
+    int host_status = 0;
+    bool ok = hipMemsetAsync(status, 0, sizeof(int), st) == hipSuccess;
+    ok = ok && launch_rank_rows(static_cast<const int32_t *>(g_idx), static_cast<int32_t *>(perm), K, group_size,
+                                status, st) == hipSuccess;
+    ok = ok && hipMemcpyAsync(&host_status, status, sizeof(int), hipMemcpyDeviceToHost, st) == hipSuccess;
+    ok = ok && hipStreamSynchronize(st) == hipSuccess;
+    (void)hipFree(status);
+    if (!ok)
+        return GPTQ_HIP_ERROR;
+    if (host_status & 1)
+        return GPTQ_INVALID_ARG;  // g_idx entry outside [0, K / group_size)
+    if (host_status & 2)
+        return GPTQ_UNSUPPORTED_SHAPE;  // a group owns more (so another fewer) than group_size rows
+    if (launch_sort_rows(static_cast<const uint32_t *>(qweight), static_cast<const int32_t *>(perm),
+                         static_cast<uint32_t *>(qweight_sorted), K, N, st) != hipSuccess)
+        return GPTQ_HIP_ERROR;
+    return hipStreamSynchronize(st) == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
+}
+
+int gptq_w4a16_gemm_prepared(const void *x, const void *qweight_sorted, const void *qzeros, const void *scales,
+                             const void *perm, void *out, int M, int K, int N, int group_size,
+                             gptq_stream_t stream)
+{
+    if (!x || !qweight_sorted || !qzeros || !scales || !perm || !out || M <= 0)
+        return GPTQ_INVALID_ARG;
+    const int rc = check_shape(K, N, group_size);
+    if (rc != GPTQ_OK)
+        return rc;
+    if (!aligned16(x) || !aligned16(qweight_sorted) || !aligned16(qzeros) || !aligned16(scales) || !aligned16(out) ||
+        !aligned16(perm))
+        return GPTQ_MISALIGNED;
+    Problem p;
+    p.x = nullptr;  // the gathered copy, below
+    p.qweight = static_cast<const uint32_t *>(qweight_sorted);
+    p.qzeros = static_cast<const uint32_t *>(qzeros);
+    p.scales = static_cast<const half_t *>(scales);
+    p.g_idx = nullptr;
+    p.out = static_cast<half_t *>(out);
+    p.M = M;
+    p.K = K;
+    p.N = N;
+    p.group_size = group_size;
+    const Resolved r = resolve(p, nullptr);
+    // scratch: what the kernel needs, then the gathered activations
+    const size_t kernel_bytes = align256(scratch_bytes(p, r));
+    void *ws = nullptr;
+    const int wrc = acquire_workspace(kernel_bytes + (size_t)M * K * sizeof(half_t), &ws);
+    if (wrc != GPTQ_OK)
+        return wrc;
+    half_t *xp = reinterpret_cast<half_t *>(static_cast<unsigned char *>(ws) + kernel_bytes);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (launch_gather_activations(static_cast<const half_t *>(x), static_cast<const int32_t *>(perm), xp, M, K, st) !=
+        hipSuccess)
+        return GPTQ_HIP_ERROR;
+    p.x = xp;
+    return launch_resolved(p, r, ws, st);
 }
 
 int gptq_w4a16_dequant(const void *qweight, const void *qzeros, const void *scales, const void *g_idx,

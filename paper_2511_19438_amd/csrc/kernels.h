@@ -30,6 +30,14 @@ hipError_t launch_unpack(const uint32_t *qweight, uint8_t *q_out, const uint32_t
 hipError_t launch_dequant(const uint32_t *qweight, const uint32_t *qzeros, const half_t *scales,
                           const int32_t *g_idx, half_t *w_out, int K, int N, int group_size, hipStream_t stream);
 
+// ---- act-order repack (one-time) and the activation gather of the repacked path ----
+// `status` is a device int that must be zero before the call; see the kernel for its bits.
+hipError_t launch_rank_rows(const int32_t *g_idx, int32_t *perm, int K, int group_size, int *status, hipStream_t stream);
+hipError_t launch_sort_rows(const uint32_t *qweight, const int32_t *perm, uint32_t *sorted, int K, int N,
+                            hipStream_t stream);
+hipError_t launch_gather_activations(const half_t *x, const int32_t *perm, half_t *xp, int M, int K,
+                                     hipStream_t stream);
+
 // ---- decode: split-K vector kernel, M <= 16 per launch ----
 struct DecodePlan {
     int cols_per_wg;   // 16, 32, 64, 128 or 256

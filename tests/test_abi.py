@@ -27,10 +27,11 @@ def declared_functions():
 
 def test_header_declares_the_expected_entry_points():
     names = declared_functions()
-    assert len(names) == len(set(names)) == 9
+    assert len(names) == len(set(names)) == 11
     for required in ("gptq_w4a16_gemm", "gptq_w4a16_dequant", "gptq_w4a16_unpack", "gptq_w4a16_workspace_bytes",
                      "gptq_w4a16_set_workspace", "gptq_w4a16_strerror", "gptq_w4a16_version",
-                     "gptq_w4a16_gemm_plan", "gptq_w4a16_plan_query"):
+                     "gptq_w4a16_gemm_plan", "gptq_w4a16_plan_query", "gptq_w4a16_act_order_prepare",
+                     "gptq_w4a16_gemm_prepared"):
         assert required in names
 
 
@@ -158,3 +159,20 @@ def test_plan_query_validates_like_the_gemm(lib):
         binding.gptq_w4a16_plan_query(1, 4100, 4096, 128)
     with pytest.raises(binding.GptqError):
         binding.gptq_w4a16_plan_query(1, 4096, 4096, 128, plan=binding.Plan(kernel=7))
+
+
+def test_repack_entry_points_validate_before_any_gpu_work(lib):
+    """NULL pointers, bad shapes and misaligned pointers are refused on the host."""
+    buf = (ctypes.c_char * 4096)()
+    base = ctypes.addressof(buf)
+    base += (-base) % 256
+    p = ctypes.c_void_p(base)
+    odd = ctypes.c_void_p(base + 4)
+    assert lib.gptq_w4a16_act_order_prepare(None, p, p, p, 128, 8, 128, None) == -1
+    assert lib.gptq_w4a16_act_order_prepare(p, p, p, p, 128, 8, 128, None) == -1   # in place
+    assert lib.gptq_w4a16_act_order_prepare(p, p, odd, p, 128, 8, 128, None) == -3
+    assert lib.gptq_w4a16_act_order_prepare(p, p, ctypes.c_void_p(base + 1024), p, 100, 8, 128, None) == -2
+    assert lib.gptq_w4a16_gemm_prepared(p, p, p, p, None, p, 1, 128, 8, 128, None) == -1
+    assert lib.gptq_w4a16_gemm_prepared(p, p, p, p, p, p, 0, 128, 8, 128, None) == -1
+    assert lib.gptq_w4a16_gemm_prepared(p, p, p, p, p, p, 1, 128, 12, 128, None) == -2
+    assert lib.gptq_w4a16_gemm_prepared(p, p, odd, p, p, p, 1, 128, 8, 128, None) == -3

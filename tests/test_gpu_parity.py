@@ -359,3 +359,77 @@ def test_scratch_survives_a_change_of_problem_width(B):
         ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
         out = run_gemm(B, case, group, B.Plan(kernel=1, split_k=4, tile=16))
         assert_within_band(out, ref, f"N={N} after other widths")
+
+
+# ------------------------------------------------------------------ act-order repack (one-time) and its GEMM
+
+REPACK_SHAPES = [(1024, 328, 128), (512, 72, 32), (2048, 1032, 128), (256, 64, 64)]
+
+
+def _repack(B, case, group):
+    qw = dev(case["qweight"])
+    qs = torch.empty_like(qw)
+    perm = torch.empty(case["g_idx"].shape[0], dtype=torch.int32, device="cuda")
+    B.gptq_w4a16_act_order_prepare(qw, dev(case["g_idx"]), qs, perm, group)
+    return qs, perm
+
+
+@pytest.mark.parametrize("K,N,group", REPACK_SHAPES)
+def test_repack_sorts_rows_by_group_bit_exact(B, K, N, group):
+    """perm is the stable order of k by g_idx; the sorted matrix dequantises, without g_idx, to the rows of the
+    oracle's act-order weights in that order."""
+    case = workloads.make_case(1, K, N, group, seed=K + N, act_order=True)
+    qs, perm = _repack(B, case, group)
+    want_perm = np.argsort(case["g_idx"], kind="stable").astype(np.int32)
+    assert np.array_equal(perm.cpu().numpy(), want_perm)
+    w_ref = oracle.dequant(case["qweight"], case["qzeros"], case["scales"], case["g_idx"], group)
+    w_out = torch.empty((K, N), dtype=torch.float16, device="cuda")
+    B.gptq_w4a16_dequant(qs, dev(case["qzeros"]), dev(case["scales"]), None, w_out, group)
+    got = w_out.cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, w_ref.view(np.uint16)[want_perm])
+    # and the codes themselves
+    q_ref = oracle.unpack_qweight(case["qweight"])
+    q_out = torch.empty((K, N), dtype=torch.uint8, device="cuda")
+    B.gptq_w4a16_unpack(qs, q_out, None, None, group)
+    assert np.array_equal(q_out.cpu().numpy(), q_ref[want_perm])
+
+
+@pytest.mark.parametrize("M", [1, 2, 8, 16, 40, 300])
+@pytest.mark.parametrize("K,N,group", REPACK_SHAPES[:3])
+def test_repacked_gemm_matches_oracle(B, M, K, N, group):
+    case = workloads.make_case(M, K, N, group, seed=7 * K + N + M, act_order=True)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], case["g_idx"], group)
+    qs, perm = _repack(B, case, group)
+    out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    B.gptq_w4a16_gemm_prepared(dev(case["x"]), qs, dev(case["qzeros"]), dev(case["scales"]), perm, out, group)
+    assert_within_band(out.cpu().numpy(), ref, f"repacked M={M} K={K} N={N} g={group}")
+
+
+def test_repacked_one_hot_rows_are_bit_exact(B):
+    K, N, group, M = 512, 136, 128, 4
+    case = workloads.make_case(M, K, N, group, seed=3, act_order=True)
+    ks = [0, 129, 300, 511]
+    case["x"] = workloads.one_hot_activations(M, K, ks)
+    w_ref = oracle.dequant(case["qweight"], case["qzeros"], case["scales"], case["g_idx"], group)
+    qs, perm = _repack(B, case, group)
+    out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    B.gptq_w4a16_gemm_prepared(dev(case["x"]), qs, dev(case["qzeros"]), dev(case["scales"]), perm, out, group)
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), w_ref.view(np.uint16)[ks])
+
+
+def test_repack_refuses_unbalanced_or_out_of_range_groups(B):
+    K, N, group = 512, 64, 128
+    case = workloads.make_case(1, K, N, group, seed=9, act_order=True)
+    qw = dev(case["qweight"])
+    qs = torch.empty_like(qw)
+    perm = torch.empty(K, dtype=torch.int32, device="cuda")
+    g = case["g_idx"].copy()
+    g[np.flatnonzero(g == 1)[0]] = 0  # group 0 now owns one row too many
+    with pytest.raises(B.GptqError) as e:
+        B.gptq_w4a16_act_order_prepare(qw, dev(g), qs, perm, group)
+    assert e.value.code == -2
+    g = case["g_idx"].copy()
+    g[5] = K // group
+    with pytest.raises(B.GptqError) as e:
+        B.gptq_w4a16_act_order_prepare(qw, dev(g), qs, perm, group)
+    assert e.value.code == -1
