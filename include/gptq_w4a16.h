@@ -84,7 +84,8 @@ typedef struct gptq_w4a16_plan {
     int kernel;      /* 0 auto, 1 vector split-K kernel (any M, processed 16 rows at a time), 2 big-tile MFMA kernel,
                         3 small-batch MFMA kernel (M <= 64, processed 32 rows at a time; no g_idx,
                         group_size % 128 == 0; else falls back) */
-    int split_k;     /* number of K slices (vector and small-batch kernels); 0 auto */
+    int split_k;     /* number of K slices (all three kernels; the big-tile kernel splits by itself only on
+                        its 128x128 and 64x128 tiles); 0 auto */
     int tile;        /* vector kernel: columns per workgroup (16, 32, 64, 128 or 256);
                         small-batch MFMA kernel: columns per workgroup (64 or 256; anything else = auto);
                         MFMA kernel: tile id 1..10 = rows x columns per workgroup (wavefront grid):
@@ -153,7 +154,9 @@ GPTQ_API int gptq_w4a16_unpack(const void *qweight, void *q_out, const void *qze
 /*
  * Split-K scratch.  gptq_w4a16_gemm needs device scratch for the partial sums of the K
  * slices and one arrival counter per column tile.  gptq_w4a16_workspace_bytes() is an
- * upper bound for a given problem (0 for invalid shapes).  If the caller never sets a
+ * upper bound for a given problem under the automatic plan, with or without g_idx (0 for invalid
+ * shapes); an explicit plan that needs more fails with GPTQ_WORKSPACE_TOO_SMALL on a caller-owned
+ * workspace.  If the caller never sets a
  * workspace the library allocates one with hipMalloc on first use and grows it when
  * needed (the only allocation it makes; growing synchronises the device).
  * gptq_w4a16_set_workspace() hands over caller-owned device memory (256-byte aligned, at

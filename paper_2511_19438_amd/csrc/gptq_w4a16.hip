@@ -130,6 +130,7 @@ Resolved resolve(const Problem &p, const gptq_w4a16_plan_t *plan)
         skinny_make_plan(p, r.skinny);
     } else {
         r.prefill.tile = plan ? plan->tile : 0;
+        r.prefill.split_k = plan ? plan->split_k : 0;
         prefill_make_plan(p, r.prefill);
     }
     return r;
@@ -141,7 +142,7 @@ size_t scratch_bytes(const Problem &p, const Resolved &r)
         return decode_workspace_bytes(p, r.decode);
     if (r.kernel == 3)
         return skinny_workspace_bytes(p, r.skinny);
-    return decode_counter_bytes(p.N);  // the big-tile MFMA kernel uses none; keep the counter area valid
+    return prefill_workspace_bytes(p, r.prefill);  // 0 unless K is split
 }
 
 int launch_resolved(const Problem &p, const Resolved &r, void *ws, hipStream_t stream)
@@ -152,7 +153,7 @@ int launch_resolved(const Problem &p, const Resolved &r, void *ws, hipStream_t s
     else if (r.kernel == 3)
         err = launch_skinny(p, r.skinny, ws, stream);
     else
-        err = launch_prefill(p, r.prefill, stream);
+        err = launch_prefill(p, r.prefill, ws, stream);
     return err == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
 }
 
@@ -160,8 +161,9 @@ int run_gemm(const Problem &p, hipStream_t stream, const gptq_w4a16_plan_t *plan
 {
     const Resolved r = resolve(p, plan);
     void *ws = nullptr;
-    if (r.kernel != 2) {
-        const int rc = acquire_workspace(scratch_bytes(p, r), &ws);
+    const size_t bytes = scratch_bytes(p, r);
+    if (bytes > 0) {
+        const int rc = acquire_workspace(bytes, &ws);
         if (rc != GPTQ_OK)
             return rc;
     }
@@ -250,7 +252,7 @@ int gptq_w4a16_plan_query(int M, int K, int N, int group_size, int act_order, co
         out.split_k = r.skinny.split_k;
         out.tile = r.skinny.cols_per_wg;
     } else {
-        out.split_k = 1;
+        out.split_k = r.prefill.split_k;
         out.tile = r.prefill.tile;
     }
     *resolved = out;
@@ -317,7 +319,10 @@ int gptq_w4a16_gemm_prepared(const void *x, const void *qweight_sorted, const vo
     p.group_size = group_size;
     const Resolved r = resolve(p, nullptr);
     // scratch: what the kernel needs, then the gathered activations
-    const size_t kernel_bytes = align256(scratch_bytes(p, r));
+    // (the counter area at the front stays reserved even if this launch needs none: it must remain zero)
+    size_t kernel_bytes = align256(scratch_bytes(p, r));
+    if (kernel_bytes < decode_counter_bytes(N))
+        kernel_bytes = decode_counter_bytes(N);
     void *ws = nullptr;
     const int wrc = acquire_workspace(kernel_bytes + (size_t)M * K * sizeof(half_t), &ws);
     if (wrc != GPTQ_OK)
@@ -394,6 +399,16 @@ size_t gptq_w4a16_workspace_bytes(int M, int K, int N, int group_size)
         const size_t sk = skinny_workspace_bytes(p, sp);
         if (sk > bytes)
             bytes = sk;
+    }
+    // the big-tile kernel splits K on few-tile shapes; counted where the default dispatch picks it
+    for (int act = 0; act < 2; ++act) {
+        p.g_idx = act ? &dummy : nullptr;
+        const Resolved r = resolve(p, nullptr);
+        if (r.kernel == 2) {
+            const size_t pf = prefill_workspace_bytes(p, r.prefill);
+            if (pf > bytes)
+                bytes = pf;
+        }
     }
     return bytes;
 }

@@ -67,10 +67,13 @@ hipError_t launch_skinny(const Problem &p, const SkinnyPlan &plan, void *workspa
 
 // ---- prefill: fp16 MFMA kernel ----
 struct PrefillPlan {
-    int tile;  // tile configuration id (1-based), 0 = auto
+    int tile;     // tile configuration id (1-based), 0 = auto
+    int split_k;  // K slices (pipelined kernel only), 0 = auto
 };
 bool prefill_supported(const Problem &p);
 void prefill_make_plan(const Problem &p, PrefillPlan &plan);
-hipError_t launch_prefill(const Problem &p, const PrefillPlan &plan, hipStream_t stream);
+// Scratch of a plan with split_k > 1 (counter area first, as for the other kernels); 0 without a split.
+size_t prefill_workspace_bytes(const Problem &p, const PrefillPlan &plan);
+hipError_t launch_prefill(const Problem &p, const PrefillPlan &plan, void *workspace, hipStream_t stream);
 
 }  // namespace gptq

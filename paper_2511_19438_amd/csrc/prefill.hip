@@ -1,6 +1,8 @@
 // Host side of the MFMA kernel: tile selection and dispatch.
 #include "prefill_kernel.h"
 
+#include <cmath>
+
 namespace gptq {
 
 namespace prefill {
@@ -21,15 +23,46 @@ template <> hipError_t launch_tile<10>(const Args &, int, hipStream_t);
 namespace {
 
 struct TileShape {
-    int bm, bn;
-    double rate;  // measured in-loop MFMA rate relative to the 256x256 tile with 2x2 wavefronts (0 = not auto-selected)
+    int bm, bn, bk;
+    double stage_us;  // one 64-k stage of a workgroup of this tile, measured (0 = tile is never auto-selected)
+    double overlap;   // how many workgroups' worth of work a compute unit does in one workgroup's time when
+                      // several are resident (small tiles: their pipelines interleave); 1 = one at a time
+    bool may_split;   // K slices pay only where a thread holds few accumulators (the combine moves them all)
 };
 // ids 1..10, see the plan documentation in the public header
-constexpr TileShape kTiles[11] = {{0, 0, 0.0},      {256, 256, 0.0},  {256, 128, 0.0},  {128, 128, 0.68},
-                                  {128, 256, 0.0},  {64, 128, 0.45},  {32, 256, 0.30},  {256, 256, 0.0},
-                                  {128, 256, 0.84}, {256, 256, 1.00}, {256, 256, 0.0}};
+constexpr TileShape kTiles[11] = {
+    {0, 0, 64, 0.0, 1.0, false},      {256, 256, 64, 0.0, 1.0, false},  {256, 128, 64, 0.0, 1.0, false},
+    {128, 128, 64, 0.85, 1.1, true},  {128, 256, 64, 0.0, 1.0, false},  {64, 128, 64, 0.455, 1.3, true},
+    {32, 256, 64, 0.75, 1.3, false},  {256, 256, 32, 0.0, 1.0, false},  {128, 256, 64, 0.99, 1.0, false},
+    {256, 256, 64, 1.47, 1.0, false}, {256, 256, 32, 0.0, 1.0, false}};
 constexpr int kNumTiles = 10;
 constexpr int kComputeUnits = 256;
+constexpr size_t kCounterBytes = 256 * 1024;  // same fixed counter area as the other kernels
+constexpr int kMaxSplit = 32;
+
+int ceil_div_i(int a, int b)
+{
+    return (a + b - 1) / b;
+}
+
+// Estimated duration (microseconds) of the pipelined kernel with tile `t` and `split` K slices.  A workgroup
+// walks its stages at a fixed pace (the pipeline is latency bound when it has a compute unit to itself, and
+// co-resident workgroups share the matrix pipe), so the chip needs ceil(workgroups / 256) such walks; a split
+// adds the scratch round trip of the combine.  Stage times measured on Llama-7B shapes, M = 48 ... 2048.
+double estimate_us(const Problem &p, int t, int split)
+{
+    const TileShape &ts = kTiles[t];
+    const int tiles = ceil_div_i(p.M, ts.bm) * ceil_div_i(p.N, ts.bn);
+    const int stages = ceil_div_i(p.K, 64);
+    const int sps = ceil_div_i(stages, split);
+    const int slices = ceil_div_i(stages, sps);
+    const double wgs = (double)tiles * slices;
+    double rounds = ts.overlap > 1.0 ? wgs / (kComputeUnits * ts.overlap) : std::ceil(wgs / kComputeUnits);
+    if (rounds < 1.0)
+        rounds = 1.0;
+    // 1.5 us to fill and drain a workgroup's pipeline, 5 us for the combine of a split
+    return 3.5 + rounds * (sps * ts.stage_us + 1.5) + (slices > 1 ? 5.0 : 0.0);
+}
 
 int mode_of(const Problem &p)
 {
@@ -51,30 +84,61 @@ void prefill_make_plan(const Problem &p, PrefillPlan &plan)
 {
     const int mode = mode_of(p);
     if (mode != prefill::kGroupPerStage) {
-        plan.tile = 3;  // the general modes exist for one tile shape only
+        plan.tile = 3;  // the general modes exist for one tile shape only, without a K split
+        plan.split_k = 1;
         return;
     }
-    if (plan.tile >= 1 && plan.tile <= kNumTiles)
+    const bool tile_given = plan.tile >= 1 && plan.tile <= kNumTiles;
+    const bool split_given = plan.split_k >= 1;
+    if (tile_given && kTiles[plan.tile].stage_us <= 0.0) {  // a tile that is only ever requested: honour it as it is
+        if (!split_given)
+            plan.split_k = 1;
         return;
-    // Pick the tile that minimises (rounds of workgroups over the chip) x (cost of one tile).
+    }
+    // Few output tiles and a deep K leave most of the chip idle and every workgroup walking all of K: K slices
+    // (combined through scratch in slice order) shorten the walk.  Cheapest (tile, split) by the estimate.
     double best = 0.0;
-    int best_tile = 3;
+    int best_tile = 3, best_split = 1;
+    const int stages = ceil_div_i(p.K, 64);
     for (int t = 1; t <= kNumTiles; ++t) {
-        const TileShape &ts = kTiles[t];
-        if (ts.rate <= 0.0)
+        if (kTiles[t].stage_us <= 0.0 || (tile_given && t != plan.tile))
             continue;
-        const long long tiles = (long long)((p.M + ts.bm - 1) / ts.bm) * ((p.N + ts.bn - 1) / ts.bn);
-        const long long rounds = (tiles + kComputeUnits - 1) / kComputeUnits;
-        const double cost = (double)rounds * ts.bm * ts.bn / ts.rate;
-        if (best == 0.0 || cost < best) {
-            best = cost;
-            best_tile = t;
+        int last_slices = 0;
+        for (int split = 1; split <= kMaxSplit && split <= stages / 2 + (stages < 2); ++split) {
+            if (split_given && split != (plan.split_k < stages ? plan.split_k : stages))
+                continue;
+            if (!split_given && split > 1 && !kTiles[t].may_split)
+                break;
+            const int slices = ceil_div_i(stages, ceil_div_i(stages, split));
+            if (slices == last_slices)
+                continue;
+            last_slices = slices;
+            const double us = estimate_us(p, t, split);
+            if (best == 0.0 || us < best - 1e-9) {
+                best = us;
+                best_tile = t;
+                best_split = slices;
+            }
         }
     }
+    if (best == 0.0) {  // a requested split beyond what the loop offers
+        best_tile = tile_given ? plan.tile : 3;
+        best_split = split_given ? plan.split_k : 1;
+    }
     plan.tile = best_tile;
+    plan.split_k = best_split;
 }
 
-hipError_t launch_prefill(const Problem &p, const PrefillPlan &plan, hipStream_t stream)
+size_t prefill_workspace_bytes(const Problem &p, const PrefillPlan &plan)
+{
+    if (plan.split_k <= 1 || plan.tile < 1 || plan.tile > kNumTiles)
+        return 0;
+    const TileShape &ts = kTiles[plan.tile];
+    const size_t tiles = (size_t)ceil_div_i(p.M, ts.bm) * ceil_div_i(p.N, ts.bn);
+    return kCounterBytes + (size_t)plan.split_k * tiles * ts.bm * ts.bn * sizeof(float);
+}
+
+hipError_t launch_prefill(const Problem &p, const PrefillPlan &plan, void *workspace, hipStream_t stream)
 {
     prefill::Args a;
     a.x = p.x;
@@ -88,6 +152,13 @@ hipError_t launch_prefill(const Problem &p, const PrefillPlan &plan, hipStream_t
     a.N = p.N;
     a.group_size = p.group_size;
     a.tiles_m = a.tiles_n = 0;
+    a.split_k = (workspace && plan.split_k > 1) ? plan.split_k : 1;
+    a.stages_per_slice = 0;
+    a.counters = reinterpret_cast<unsigned *>(workspace);
+    a.partial = workspace ? reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + kCounterBytes) : nullptr;
+    if (a.split_k > 1 && (size_t)ceil_div_i(p.M, kTiles[plan.tile].bm) * ceil_div_i(p.N, kTiles[plan.tile].bn) >
+                             kCounterBytes / sizeof(unsigned))
+        a.split_k = 1;  // more tiles than arrival counters: such a problem needs no split anyway
     const int mode = mode_of(p);
     switch (plan.tile) {
     case 1: return prefill::launch_tile<1>(a, mode, stream);

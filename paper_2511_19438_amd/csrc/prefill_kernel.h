@@ -60,6 +60,12 @@ struct Args {
     half_t *out;
     int M, K, N, group_size;
     int tiles_m, tiles_n;
+    // K split of the pipelined kernel (few output tiles, deep K): slice s of a tile covers the stages
+    // [s * stages_per_slice, ...); the slices meet in scratch, in slice order, as in the other kernels.
+    int split_k;            // 1 = no split
+    int stages_per_slice;
+    float *partial;         // [split_k][tiles][accumulators per thread][256 threads] fp32
+    unsigned *counters;     // [tiles], zero between launches
 };
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
@@ -113,11 +119,15 @@ __device__ __forceinline__ u32x4_t dequant_word(uint32_t w, const PairMagic &k, 
 
 // XCD-aware tile order: workgroup ids congruent mod 8 run on one XCD; give each XCD a contiguous range
 // of the (m fastest) tile order.  Returns false for the padding workgroups of the last range.
-__device__ __forceinline__ bool tile_of_workgroup(const Args &a, int &tile_m, int &tile_n)
+// With a K split the grid is `split_k` such ranges one after the other (the slices of a tile share an XCD).
+__device__ __forceinline__ bool tile_of_workgroup(const Args &a, int &tile_m, int &tile_n, int &logical, int &slice)
 {
     const int total = a.tiles_m * a.tiles_n;
     const int per_xcd = (total + 7) / 8;
-    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const int padded = per_xcd * 8;
+    slice = blockIdx.x / padded;
+    const int inner = blockIdx.x - slice * padded;
+    logical = (inner & 7) * per_xcd + (inner >> 3);
     if (logical >= total)
         return false;
     tile_m = logical % a.tiles_m;
@@ -201,14 +211,16 @@ __global__ __launch_bounds__(kThreads) void prefill_pipelined_kernel(const Args 
     const int lj = lane & 31;
     const int kh = lane >> 5;
 
-    int tile_m, tile_n;
-    if (!tile_of_workgroup(a, tile_m, tile_n))
+    int tile_m, tile_n, tile_id, slice;
+    if (!tile_of_workgroup(a, tile_m, tile_n, tile_id, slice))
         return;
     const int m0 = tile_m * BM;
     const int n0 = tile_n * BN;
     const int N = a.N, K = a.K, M = a.M;
-    const int stages = K / BK;  // K is a multiple of the group size, which is a multiple of 64
-    const int last = stages - 1;
+    const int all_stages = K / BK;  // K is a multiple of the group size, which is a multiple of 64
+    const int first = slice * a.stages_per_slice;  // this workgroup's stages: [first, first + stages)
+    const int stages = min(a.stages_per_slice, all_stages - first);
+    const int last = first + stages - 1;
     const int col_local = wn * WAVE_N + TN * lj;  // first of this lane's TN columns inside the tile
     const int col_raw = n0 + col_local;
     const bool col_ok = col_raw < N;
@@ -257,7 +269,7 @@ __global__ __launch_bounds__(kThreads) void prefill_pipelined_kernel(const Args 
     const int stages_per_group = a.group_size / BK;
 
     // The stage whose loads are issued next, kept incrementally (no division in the loop).
-    int ld_stage = 0, ld_group = 0, ld_in_group = 0;
+    int ld_stage = first, ld_group = first / stages_per_group, ld_in_group = first % stages_per_group;
     auto stage_base = [&](int ring) { return smem + (size_t)ring * L::BYTES; };
     // piece `p` (0 .. LOADS_PER_STAGE-1) of the loads of stage `ld_stage` into ring slot `ring`
     auto issue_piece = [&](int p, int ring) {
@@ -444,6 +456,54 @@ __global__ __launch_bounds__(kThreads) void prefill_pipelined_kernel(const Args 
     // nothing may still be writing this workgroup's LDS when it retires
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
+    if (a.split_k > 1) {
+        // ---- combine the K slices: every slice leaves its accumulators in scratch (element e of thread t at
+        //      [e][t]: coalesced), the last workgroup of the tile to arrive adds them in slice order.  Device
+        //      scope accesses and an arrival counter, no device-wide fence (see the vector kernel). ----
+        constexpr int ACC = TM * TN * 16;
+        __shared__ int s_last;
+        const size_t tiles = (size_t)a.tiles_m * a.tiles_n;
+        float *mine = a.partial + ((size_t)slice * tiles + tile_id) * ACC * kThreads + tid;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int t = 0; t < TN; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    __hip_atomic_store(mine + (size_t)((i * TN + t) * 16 + r) * kThreads, acc[i][t][r],
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);  // every partial store of this workgroup has been acknowledged
+        __syncthreads();
+        if (tid == 0) {
+            const unsigned prev =
+                __hip_atomic_fetch_add(a.counters + tile_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = (prev == (unsigned)(a.split_k - 1));
+        }
+        __syncthreads();
+        if (!s_last)
+            return;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int t = 0; t < TN; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    acc[i][t][r] = 0.f;
+        for (int sl = 0; sl < a.split_k; ++sl) {
+            const float *theirs = a.partial + ((size_t)sl * tiles + tile_id) * ACC * kThreads + tid;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int t = 0; t < TN; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc[i][t][r] += __hip_atomic_load(theirs + (size_t)((i * TN + t) * 16 + r) * kThreads,
+                                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (tid == 0)
+            __hip_atomic_store(a.counters + tile_id, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+    }
     store_tile<TM, TN>(acc, a.out, m0 + wm * WAVE_M, col_raw, col_ok, kh, M, N);
 }
 
@@ -479,7 +539,8 @@ __global__ __launch_bounds__(kThreads) void prefill_general_kernel(const Args a)
     const int kh = lane >> 5;
 
     int tile_m, tile_n;
-    if (!tile_of_workgroup(a, tile_m, tile_n))
+    int tile_id, slice;
+    if (!tile_of_workgroup(a, tile_m, tile_n, tile_id, slice))
         return;
     const int m0 = tile_m * BM;
     const int n0 = tile_n * BN;

@@ -40,12 +40,18 @@ constexpr int BM = 256, BN = 256, WM = 2, WN = 2, BK = 32, NBUF = 6;
 #endif
 
 template <typename Kernel>
-hipError_t launch(Kernel kernel, Args a, size_t lds, hipStream_t stream)
+hipError_t launch(Kernel kernel, Args a, size_t lds, bool may_split, hipStream_t stream)
 {
     a.tiles_m = (a.M + BM - 1) / BM;
     a.tiles_n = (a.N + BN - 1) / BN;
     const int total = a.tiles_m * a.tiles_n;
-    const unsigned grid = 8u * (unsigned)((total + 7) / 8);
+    // the requested split, in whole stages of this tile's BK
+    const int all_stages = (a.K + BK - 1) / BK;
+    int split = (may_split && a.split_k > 1) ? (a.split_k < all_stages ? a.split_k : all_stages) : 1;
+    a.stages_per_slice = (all_stages + split - 1) / split;
+    split = (all_stages + a.stages_per_slice - 1) / a.stages_per_slice;
+    a.split_k = split;
+    const unsigned grid = 8u * (unsigned)((total + 7) / 8) * (unsigned)split;
     if (lds > 48 * 1024) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -63,13 +69,13 @@ hipError_t launch_tile<GPTQ_PREFILL_TILE>(const Args &a, int mode, hipStream_t s
 {
     if (mode == kGroupPerStage)
         return launch(prefill_pipelined_kernel<BM, BN, WM, WN, BK, NBUF>, a,
-                      (size_t)NBUF * StageLayout<BM, BN, BK>::BYTES, stream);
+                      (size_t)NBUF * StageLayout<BM, BN, BK>::BYTES, true, stream);
 #if GPTQ_PREFILL_TILE == 3
     const size_t lds = 2 * (size_t)BM * 64 * sizeof(half_t);
     if (mode == kGroupPerRow)
-        return launch(prefill_general_kernel<BM, BN, WM, WN, kGroupPerRow>, a, lds, stream);
+        return launch(prefill_general_kernel<BM, BN, WM, WN, kGroupPerRow>, a, lds, false, stream);
     if (mode == kActOrder)
-        return launch(prefill_general_kernel<BM, BN, WM, WN, kActOrder>, a, lds, stream);
+        return launch(prefill_general_kernel<BM, BN, WM, WN, kActOrder>, a, lds, false, stream);
 #endif
     return hipErrorInvalidValue;
 }

@@ -207,6 +207,24 @@ def test_prefill_tiles_match_oracle(B, tile, M, N):
     assert_within_band(out, ref, f"prefill tile={tile} M={M} N={N}")
 
 
+@pytest.mark.parametrize("tile", [1, 3, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("split_k", [2, 3, 7, 32])
+@pytest.mark.parametrize("M,N", [(300, 544), (40, 288)])
+def test_prefill_k_split_matches_oracle(B, tile, split_k, M, N):
+    """K slices of the big-tile kernel (slices that end inside a group, a ragged last slice, more slices
+    requested than stages), combined through scratch; twice in a row: the arrival counters must be back at zero."""
+    K, group = 1408, 128   # 22 stages of 64 k
+    case = workloads.make_case(M, K, N, group, seed=tile + M + split_k)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    plan = B.Plan(kernel=2, tile=tile, split_k=split_k)
+    res = B.gptq_w4a16_plan_query(M, K, N, group, False, plan)
+    assert res.kernel == 2 and res.tile == tile and res.split_k >= 2
+    first = run_gemm(B, case, group, plan)
+    again = run_gemm(B, case, group, plan)
+    assert_within_band(first, ref, f"prefill tile={tile} split={split_k} M={M} N={N}")
+    assert np.array_equal(first.view(np.uint16), again.view(np.uint16))
+
+
 def test_mfma_kernel_also_serves_small_batches_when_asked(B):
     M, K, N, group = 3, 512, 264, 128
     case = workloads.make_case(M, K, N, group, seed=8)
