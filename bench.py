@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill (MFMA) leg")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-context", action="store_true", help="skip the device-copy / dense-matmul context lines")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the batch-size / act-order / 70B side tables")
+    ap.add_argument("--ablation", action="store_true",
+                    help="also time the vector kernel with each of the paper's three techniques taken out")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference kernel for the HBM traffic counters)")
     args = ap.parse_args()
@@ -189,9 +192,116 @@ def main():
     if prefill:
         line["prefill"] = prefill["summary"]
         line["roofline_prefill"] = prefill["roofline"]
+    if not args.no_sweep:
+        line["sweep"] = sweep_tables(torch, B, workloads, layers)
+    if args.ablation:
+        line["ablation"] = ablation_table(torch, B, workloads, layers)
     if not args.no_context:
         line["context"] = context_lines(torch)
     print(json.dumps(line))
+
+
+def graph_us(torch, launches, reps=6):
+    """Mean microseconds per launch of a list of zero-argument launch functions, replayed as one HIP graph."""
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for f in launches:
+            f()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for f in launches:
+                f()
+        graph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            graph.replay()
+        e1.record(stream)
+        torch.cuda.synchronize()
+    del graph
+    return e0.elapsed_time(e1) * 1e3 / (reps * len(launches))
+
+
+def sweep_tables(torch, B, workloads, layers):
+    """Side tables (not the headline): the decode batch sweep on the Llama-7B shapes, the act-order layer with
+    its g_idx kernels and repacked, and single-row GEMVs on the Llama-70B shapes.  Every launch streams its
+    weights from HBM (the launches of a graph rotate over distinct weight copies larger than the caches)."""
+    shapes = workloads.LLAMA_7B
+    out = {"unit": "us per launch (GB/s of algorithmic bytes)", "llama7b": [], "act_order": [], "llama70b": []}
+    for si, sh in enumerate(shapes):
+        row = {"shape": f"{sh.name} K={sh.K} N={sh.N}"}
+        for M in workloads.DECODE_BATCHES:
+            x = torch.randn((M, sh.K), device="cuda").half()
+            o = torch.empty((M, sh.N), dtype=torch.float16, device="cuda")
+            fns = [(lambda t=mats[si]: B.gptq_w4a16_gemm(x, t["qweight"], t["qzeros"], t["scales"], None, o, GROUP))
+                   for mats in layers]
+            us = graph_us(torch, fns)
+            row[f"M={M}"] = [round(us, 2), round(algorithmic_bytes(M, sh.K, sh.N) / us / 1e3)]
+        out["llama7b"].append(row)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234)
+
+    def device_weights(K, N, copies):
+        qws = [torch.randint(-2**31, 2**31 - 1, (K // 8, N), dtype=torch.int32, device="cuda", generator=gen)
+               for _ in range(copies)]
+        qz = torch.randint(-2**31, 2**31 - 1, (K // GROUP, N // 8), dtype=torch.int32, device="cuda", generator=gen)
+        sc = (torch.rand((K // GROUP, N), device="cuda", generator=gen) * 0.009 + 0.001).half()
+        return qws, qz, sc
+
+    # act-order layer (rows of a group scattered over K): the kernels that look g_idx up per row, and the same
+    # layer after the one-time repack
+    sh = workloads.ACT_ORDER_SHAPE
+    copies = 24
+    qws, qz, sc = device_weights(sh.K, sh.N, copies)
+    g_idx = (torch.randperm(sh.K, device="cuda", generator=gen) // GROUP).int()
+    sorted_qws = [torch.empty_like(q) for q in qws]
+    perm = torch.empty(sh.K, dtype=torch.int32, device="cuda")
+    for q, qs in zip(qws, sorted_qws):
+        B.gptq_w4a16_act_order_prepare(q, g_idx, qs, perm, GROUP)
+    for M in (1, 8):
+        x = torch.randn((M, sh.K), device="cuda").half()
+        o = torch.empty((M, sh.N), dtype=torch.float16, device="cuda")
+        a = graph_us(torch, [(lambda q=q: B.gptq_w4a16_gemm(x, q, qz, sc, g_idx, o, GROUP)) for q in qws])
+        b = graph_us(torch, [(lambda q=q: B.gptq_w4a16_gemm_prepared(x, q, qz, sc, perm, o, GROUP)) for q in sorted_qws])
+        nbytes = algorithmic_bytes(M, sh.K, sh.N, act_order=True)
+        out["act_order"].append({"shape": f"K={sh.K} N={sh.N} M={M}", "g_idx_kernel": [round(a, 2), round(nbytes / a / 1e3)],
+                                 "repacked": [round(b, 2), round(nbytes / b / 1e3)]})
+    del qws, sorted_qws
+    torch.cuda.empty_cache()
+    for sh in workloads.LLAMA_70B:
+        copies = max(2, int(1.3e9 // (sh.K * sh.N // 2)) + 1)
+        qws, qz, sc = device_weights(sh.K, sh.N, copies)
+        row = {"shape": f"{sh.name} K={sh.K} N={sh.N}"}
+        for M in (1, 16):
+            x = torch.randn((M, sh.K), device="cuda").half()
+            o = torch.empty((M, sh.N), dtype=torch.float16, device="cuda")
+            us = graph_us(torch, [(lambda q=q: B.gptq_w4a16_gemm(x, q, qz, sc, None, o, GROUP)) for q in qws])
+            gbs = algorithmic_bytes(M, sh.K, sh.N) / us / 1e3
+            row[f"M={M}"] = [round(us, 2), round(gbs), round(gbs / HBM_PEAK_GBS, 3)]
+        out["llama70b"].append(row)
+        del qws
+        torch.cuda.empty_cache()
+    return out
+
+
+def ablation_table(torch, B, workloads, layers):
+    """The vector kernel at M = 1 with each of the paper's three techniques taken out (and all of them): on-chip
+    hierarchical reduction (SMB, Section 3.1), vectorised activation loads (VML, Section 3.2), packed half
+    arithmetic (ILA, Section 3.3).  All variants on 64-column tiles with the same automatic K split."""
+    names = {0: "all_on", 1: "no_smb", 2: "no_vml", 4: "no_ila", 7: "none_on"}
+    out = {"unit": "us per launch", "M": 1, "rows": []}
+    x_cache = {}
+    for si, sh in enumerate(workloads.LLAMA_7B):
+        row = {"shape": f"{sh.name} K={sh.K} N={sh.N}"}
+        for flags, name in names.items():
+            plan = B.Plan(kernel=1, tile=64, flags=flags)
+            fns = [(lambda t=mats[si]: B.gptq_w4a16_gemm(t["x"], t["qweight"], t["qzeros"], t["scales"], None, t["out"],
+                                                         GROUP, plan)) for mats in layers]
+            row[name] = round(graph_us(torch, fns), 2)
+        out["rows"].append(row)
+    return out
 
 
 def measured_traffic(key):

@@ -80,6 +80,10 @@ GPTQ_API int gptq_w4a16_gemm(const void *x, const void *qweight, const void *qze
  * Launch plan for gptq_w4a16_gemm_plan(): selects the kernel and its decomposition
  * explicitly (for tuning sweeps).  A zero field means "let the library choose".
  */
+#define GPTQ_ABLATE_SMB 1
+#define GPTQ_ABLATE_VML 2
+#define GPTQ_ABLATE_ILA 4
+
 typedef struct gptq_w4a16_plan {
     int kernel;      /* 0 auto, 1 vector split-K kernel (any M, processed 16 rows at a time), 2 big-tile MFMA kernel,
                         3 small-batch MFMA kernel (M <= 64, processed 32 rows at a time; no g_idx,
@@ -92,7 +96,15 @@ typedef struct gptq_w4a16_plan {
                         1 256x256 (1x4), 2 256x128 (2x2), 3 128x128 (2x2), 4 128x256 (1x4, deep ring),
                         5 64x128 (1x4), 6 32x256 (1x4), 7 256x256 (1x4, 32-k stages), 8 128x256 (1x4),
                         9 256x256 (2x2), 10 256x256 (2x2, 32-k stages); 0 auto */
-    int flags;       /* must be zero */
+    int flags;       /* 0, or (vector kernel only: M <= 4, no g_idx, group_size % 32 == 0, 64-column tiles) a set
+                        of ablation switches that take one of the paper's techniques out each, for measuring its
+                        gain in isolation (Table 3's columns at kernel level):
+                        1 GPTQ_ABLATE_SMB  no on-chip reduction (Section 3.1): every lane adds its partial sums to
+                                           memory with fp32 atomics (order of additions, hence the last bits,
+                                           not reproducible), one extra launch zeroes the sums;
+                        2 GPTQ_ABLATE_VML  activations staged with 16-bit instead of 128-bit loads (Section 3.2);
+                        4 GPTQ_ABLATE_ILA  per-weight fp32 conversion and scalar multiply-add instead of packed
+                                           half arithmetic (Section 3.3) */
     int reserved[4]; /* must be zero */
 } gptq_w4a16_plan_t;
 

@@ -84,7 +84,8 @@ void decode_make_plan(const Problem &p, DecodePlan &plan)
     const bool act = p.g_idx != nullptr;
     const int gr = p.group_size / 8;
     plan.chunk_rows = act ? 4 : (gr % 4 == 0 ? 4 : (gr % 2 == 0 ? 2 : 1));
-    const bool fixed_shape = act || plan.chunk_rows != 4;  // these variants exist for 64-column tiles only
+    // these variants (and the ablation ones) exist for 64-column tiles only
+    const bool fixed_shape = act || plan.chunk_rows != 4 || plan.flags != 0;
     const int c = plan.cols_per_wg;
     const bool tile_given = (c == 16 || c == 32 || c == 64 || c == 128 || c == 256) && !fixed_shape;
 
@@ -159,7 +160,25 @@ size_t decode_workspace_bytes(const Problem &p, const DecodePlan &plan)
     size_t bytes = decode_counter_bytes(p.N);
     if (plan.split_k > 1)
         bytes += (size_t)plan.split_k * m * p.N * sizeof(float);
+    else if (plan.flags & decode::kNoSmb)
+        bytes += (size_t)m * p.N * sizeof(float);  // the fp32 sums the lanes add into
     return bytes;
+}
+
+namespace {
+
+__global__ void zero_floats_kernel(float *p, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n)
+        p[i] = 0.f;
+}
+
+}  // namespace
+
+bool decode_ablation_supported(const Problem &p)
+{
+    return p.g_idx == nullptr && p.M <= 4 && p.group_size % 32 == 0;
 }
 
 hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspace, hipStream_t stream)
@@ -214,13 +233,20 @@ hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspa
         if (lds > kMaxLdsBytes)
             return hipErrorInvalidValue;
 
+        if (plan.flags & decode::kNoSmb) {  // the baseline accumulates into memory: it needs zeros first
+            const size_t n = (size_t)m * p.N;
+            hipLaunchKernelGGL(zero_floats_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, a.partial,
+                               n);
+            if (hipGetLastError() != hipSuccess)
+                return hipErrorLaunchFailure;
+        }
         hipError_t err;
         switch (mb) {
-        case 1: err = decode::launch_mb<1>(a, d.lpr, plan.chunk_rows, act, lds, stream); break;
-        case 2: err = decode::launch_mb<2>(a, d.lpr, plan.chunk_rows, act, lds, stream); break;
-        case 4: err = decode::launch_mb<4>(a, d.lpr, plan.chunk_rows, act, lds, stream); break;
-        case 8: err = decode::launch_mb<8>(a, d.lpr, plan.chunk_rows, act, lds, stream); break;
-        default: err = decode::launch_mb<16>(a, d.lpr, plan.chunk_rows, act, lds, stream); break;
+        case 1: err = decode::launch_mb<1>(a, d.lpr, plan.chunk_rows, act, plan.flags, lds, stream); break;
+        case 2: err = decode::launch_mb<2>(a, d.lpr, plan.chunk_rows, act, plan.flags, lds, stream); break;
+        case 4: err = decode::launch_mb<4>(a, d.lpr, plan.chunk_rows, act, plan.flags, lds, stream); break;
+        case 8: err = decode::launch_mb<8>(a, d.lpr, plan.chunk_rows, act, plan.flags, lds, stream); break;
+        default: err = decode::launch_mb<16>(a, d.lpr, plan.chunk_rows, act, plan.flags, lds, stream); break;
         }
         if (err != hipSuccess)
             return err;

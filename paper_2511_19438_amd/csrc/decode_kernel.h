@@ -123,9 +123,21 @@ __device__ __forceinline__ float load_device_scope(const float *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-template <int MB, int LPR, int R, bool ACT>
+// Ablation switches (template parameter ABL, a bit set; 0 = the kernel as designed).  Each bit takes one of
+// the paper's three techniques out and puts the baseline it describes in its place, so that the gain of the
+// technique on this chip can be measured in isolation (Table 3 has the same columns end to end):
+//   kNoSmb: no on-chip hierarchical reduction (Section 3.1) - every lane commits its partial sums straight to
+//           global memory with floating point atomics (Eq. 9-10 at thread level); the sums need a zeroed fp32
+//           buffer and a conversion by the last workgroup of the column tile;
+//   kNoVml: activations are staged with one 16-bit load per element instead of 128-bit loads (Section 3.2);
+//   kNoIla: every weight is converted to fp32 on its own and multiplied-added with scalar fp32 instructions
+//           instead of packed half conversion and v_dot2_f32_f16 (Section 3.3).
+constexpr int kNoSmb = 1, kNoVml = 2, kNoIla = 4;
+
+template <int MB, int LPR, int R, bool ACT, int ABL = 0>
 __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
 {
+    static_assert(ABL == 0 || (!ACT && MB < 8), "the ablation variants exist for the plain format at small batch");
     constexpr int RL = 64 / LPR;          // row lanes per wavefront
     constexpr int RW = kWaves * RL;       // row lanes per workgroup
     constexpr int CT = LPR * 4;           // columns per workgroup
@@ -214,6 +226,10 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
         const int m = MB == 1 ? 0 : i / rows_p;
         const int row = i - m * rows_p;
         const half_t *src = a.x + (size_t)min(m, a.M - 1) * a.K + kbeg + min(row, rows_s - 1) * 8;
+        if (ABL & kNoVml) {  // eight separate 16-bit loads (volatile: not to be merged)
+            const volatile half_t *v = src;
+            return half8_t{v[0], v[1], v[2], v[3], v[4], v[5], v[6], v[7]};
+        }
         return *reinterpret_cast<const half8_t *>(src);
     };
     auto x_store = [&](int i, half8_t h) {
@@ -311,6 +327,28 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
             for (int rr = 0; rr < R; ++rr) {
                 const uint32_t w[4] = {r.wq[j][rr].x, r.wq[j][rr].y, r.wq[j][rr].z, r.wq[j][rr].w};
                 half2_t d[4][4];
+                if (ABL & kNoIla) {
+                    // baseline arithmetic: per weight a bit-field extract, an integer-to-float conversion, the
+                    // zero point and the scale in fp32, one fp32 multiply-add per batch row
+#pragma unroll
+                    for (int m = 0; m < MB; ++m) {
+                        const uint4 xv = *reinterpret_cast<const uint4 *>(xchunk + m * Ls + rr * 8);
+                        const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w};
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            // activation k = i of the packed row sits at position 2*i (i < 4) or 2*(i-4)+1
+                            const int pos = i < 4 ? 2 * i : 2 * (i - 4) + 1;
+                            const uint16_t hb = (uint16_t)(xw[pos >> 1] >> (16 * (pos & 1)));
+                            const float xf = (float)__builtin_bit_cast(half_t, hb);
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                const float qf = (float)((w[c] >> (4 * i)) & 15u);
+                                acc[m][c] = __builtin_fmaf(xf, (qf - zf[c]) * sf[c], acc[m][c]);
+                            }
+                        }
+                    }
+                    continue;
+                }
                 if (FACTORED) {
 #pragma unroll
                     for (int c = 0; c < 4; ++c)
@@ -364,7 +402,7 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
                     }
                 }
             }
-            if (FACTORED) {
+            if (FACTORED && !(ABL & kNoIla)) {
 #pragma unroll
                 for (int m = 0; m < MB; ++m) {
                     const float2 bs = xc[m * nchunks + ul];
@@ -411,6 +449,40 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
         } else {
             consume(t, ra);
         }
+    }
+
+    if (ABL & kNoSmb) {
+        // baseline commit: every lane adds its partial sums to the (zeroed) fp32 buffer with atomics; the last
+        // workgroup of the column tile converts and clears the buffer
+        if (n0 < N) {
+#pragma unroll
+            for (int m = 0; m < MB; ++m)
+                if (m < a.M)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        __hip_atomic_fetch_add(a.partial + (size_t)m * N + n0 + c, acc[m][c], __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (tid == 0) {
+            const unsigned prev =
+                __hip_atomic_fetch_add(a.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = (prev == (unsigned)(a.split_k - 1));
+        }
+        __syncthreads();
+        if (s_last) {
+            for (int i = tid; i < a.M * CT; i += kThreads) {
+                const int m = i / CT;
+                const int n = tile * CT + (i - m * CT);
+                if (n < N)
+                    a.out[(size_t)m * N + n] = (half_t)load_device_scope(a.partial + (size_t)m * N + n);
+            }
+            if (tid == 0)
+                __hip_atomic_store(a.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        return;
     }
 
     // ---- reduce over the row lanes of a wavefront (shuffles), then over wavefronts (LDS) ----
@@ -495,7 +567,8 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
 
 // Host-side launcher of one batch size (defined once per MB in decode_mb.hip).
 template <int MB>
-hipError_t launch_mb(const Args &a, int lpr, int chunk_rows, bool act, size_t lds_bytes, hipStream_t stream);
+hipError_t launch_mb(const Args &a, int lpr, int chunk_rows, bool act, int ablate, size_t lds_bytes,
+                     hipStream_t stream);
 
 }  // namespace decode
 }  // namespace gptq

@@ -11,10 +11,10 @@ namespace decode {
 
 namespace {
 
-template <int MB, int LPR, int R, bool ACT>
+template <int MB, int LPR, int R, bool ACT, int ABL = 0>
 hipError_t launch_one(const Args &a, size_t lds_bytes, hipStream_t stream)
 {
-    auto kernel = decode_kernel<MB, LPR, R, ACT>;
+    auto kernel = decode_kernel<MB, LPR, R, ACT, ABL>;
     if (lds_bytes > 48 * 1024) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -28,10 +28,29 @@ hipError_t launch_one(const Args &a, size_t lds_bytes, hipStream_t stream)
 }  // namespace
 
 template <>
-hipError_t launch_mb<GPTQ_DECODE_MB>(const Args &a, int lpr, int chunk_rows, bool act, size_t lds_bytes,
+hipError_t launch_mb<GPTQ_DECODE_MB>(const Args &a, int lpr, int chunk_rows, bool act, int ablate, size_t lds_bytes,
                                      hipStream_t stream)
 {
     constexpr int MB = GPTQ_DECODE_MB;
+    if (ablate != 0) {
+        // the ablation variants exist for the default tile shape of the plain format, up to four rows
+#if GPTQ_DECODE_MB <= 4
+        if (act || lpr != 16 || chunk_rows != 4)
+            return hipErrorInvalidValue;
+        switch (ablate) {
+        case 1: return launch_one<MB, 16, 4, false, 1>(a, lds_bytes, stream);
+        case 2: return launch_one<MB, 16, 4, false, 2>(a, lds_bytes, stream);
+        case 3: return launch_one<MB, 16, 4, false, 3>(a, lds_bytes, stream);
+        case 4: return launch_one<MB, 16, 4, false, 4>(a, lds_bytes, stream);
+        case 5: return launch_one<MB, 16, 4, false, 5>(a, lds_bytes, stream);
+        case 6: return launch_one<MB, 16, 4, false, 6>(a, lds_bytes, stream);
+        case 7: return launch_one<MB, 16, 4, false, 7>(a, lds_bytes, stream);
+        default: return hipErrorInvalidValue;
+        }
+#else
+        return hipErrorInvalidValue;
+#endif
+    }
     if (act) {
         if (lpr == 16 && chunk_rows == 4)
             return launch_one<MB, 16, 4, true>(a, lds_bytes, stream);

@@ -123,6 +123,7 @@ Resolved resolve(const Problem &p, const gptq_w4a16_plan_t *plan)
     if (kernel == 1) {
         r.decode.cols_per_wg = plan ? plan->tile : 0;
         r.decode.split_k = plan ? plan->split_k : 0;
+        r.decode.flags = plan ? plan->flags : 0;
         decode_make_plan(p, r.decode);
     } else if (kernel == 3) {
         r.skinny.cols_per_wg = plan ? plan->tile : 0;
@@ -179,7 +180,10 @@ int check_plan(const gptq_w4a16_plan_t *plan)
 {
     if (!plan)
         return GPTQ_OK;
-    if (plan->kernel < 0 || plan->kernel > 3 || plan->split_k < 0 || plan->tile < 0 || plan->flags != 0)
+    if (plan->kernel < 0 || plan->kernel > 3 || plan->split_k < 0 || plan->tile < 0)
+        return GPTQ_INVALID_ARG;
+    // the ablation switches belong to the vector kernel
+    if (plan->flags < 0 || plan->flags > 7 || (plan->flags != 0 && plan->kernel != 1))
         return GPTQ_INVALID_ARG;
     for (int i = 0; i < 4; ++i)
         if (plan->reserved[i] != 0)
@@ -216,6 +220,8 @@ int gptq_w4a16_gemm_plan(const void *x, const void *qweight, const void *qzeros,
     p.K = K;
     p.N = N;
     p.group_size = group_size;
+    if (plan && plan->flags != 0 && !decode_ablation_supported(p))
+        return GPTQ_UNSUPPORTED_SHAPE;
     return run_gemm(p, static_cast<hipStream_t>(stream), plan);
 }
 
@@ -242,12 +248,15 @@ int gptq_w4a16_plan_query(int M, int K, int N, int group_size, int act_order, co
     p.K = K;
     p.N = N;
     p.group_size = group_size;
+    if (request && request->flags != 0 && !decode_ablation_supported(p))
+        return GPTQ_UNSUPPORTED_SHAPE;
     const Resolved r = resolve(p, request);
     gptq_w4a16_plan_t out = {};
     out.kernel = r.kernel;
     if (r.kernel == 1) {
         out.split_k = r.decode.split_k;
         out.tile = r.decode.cols_per_wg;
+        out.flags = r.decode.flags;
     } else if (r.kernel == 3) {
         out.split_k = r.skinny.split_k;
         out.tile = r.skinny.cols_per_wg;

@@ -44,7 +44,7 @@ struct DecodePlan {
     int split_k;       // number of K slices
     int chunk_rows;    // packed rows handled per lane per step (1, 2 or 4), divides group_size/8
     int chunks_per_slice;
-    int flags;
+    int flags;         // ablation switches (bit 0: no on-chip reduction, 1: scalar activation loads, 2: scalar fp32 math)
 };
 // Fills `plan` (honouring non-zero requests in it) for the problem.
 void decode_make_plan(const Problem &p, DecodePlan &plan);
@@ -52,6 +52,8 @@ void decode_make_plan(const Problem &p, DecodePlan &plan);
 size_t decode_workspace_bytes(const Problem &p, const DecodePlan &plan);
 size_t decode_counter_bytes(int N);
 hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspace, hipStream_t stream);
+// Whether the ablation variants of the vector kernel (DecodePlan::flags != 0) exist for this problem.
+bool decode_ablation_supported(const Problem &p);
 
 // ---- small batch: MFMA kernel with the vector kernel's split-K decomposition, M <= 64 ----
 constexpr int kSkinnyMaxM = 64;

@@ -80,8 +80,15 @@ def test_plan_validation(lib):
     p = ctypes.c_void_p(0x1000)
     bad = binding.Plan(kernel=4)
     assert lib.gptq_w4a16_gemm_plan(p, p, p, p, None, p, 1, 128, 8, 128, None, ctypes.byref(bad)) == -1
-    bad = binding.Plan(flags=1)
-    assert lib.gptq_w4a16_gemm_plan(p, p, p, p, None, p, 1, 128, 8, 128, None, ctypes.byref(bad)) == -1
+    # the ablation switches belong to the vector kernel, have three bits and exist for small plain problems
+    for bad in (binding.Plan(flags=1), binding.Plan(kernel=2, flags=1), binding.Plan(kernel=1, flags=8),
+                binding.Plan(kernel=1, flags=-1)):
+        assert lib.gptq_w4a16_gemm_plan(p, p, p, p, None, p, 1, 128, 8, 128, None, ctypes.byref(bad)) == -1
+    ok = binding.Plan(kernel=1, flags=5)
+    assert lib.gptq_w4a16_gemm_plan(p, p, p, p, None, p, 5, 128, 8, 128, None, ctypes.byref(ok)) == -2   # M > 4
+    assert lib.gptq_w4a16_gemm_plan(p, p, p, p, p, p, 1, 128, 8, 128, None, ctypes.byref(ok)) == -2      # g_idx
+    res = binding.gptq_w4a16_plan_query(1, 4096, 12288, 128, plan=ok)
+    assert (res.kernel, res.tile, res.flags) == (1, 64, 5)
     bad = binding.Plan()
     bad.reserved[2] = 7
     assert lib.gptq_w4a16_gemm_plan(p, p, p, p, None, p, 1, 128, 8, 128, None, ctypes.byref(bad)) == -1

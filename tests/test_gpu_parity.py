@@ -164,6 +164,19 @@ def test_decode_deep_slices(B, M, K, split_k):
         assert_within_band(out, ref, f"deep slice M={M} K={K} tile={tile}")
 
 
+@pytest.mark.parametrize("flags", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("M,split_k", [(1, 0), (1, 3), (3, 1), (4, 2)])
+def test_ablation_variants_match_oracle(B, flags, M, split_k):
+    """Each of the paper's three techniques taken out in turn (and together): the baselines they replace
+    compute the same result, inside the same band (the atomic commit adds in no fixed order)."""
+    K, N, group = 2048, 776, 128
+    case = workloads.make_case(M, K, N, group, seed=900 + M)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    for _ in range(2):  # twice: the arrival counters must be back at zero, the sums zeroed again
+        out = run_gemm(B, case, group, B.Plan(kernel=1, split_k=split_k, flags=flags))
+        assert_within_band(out, ref, f"ablation flags={flags} M={M} split={split_k}")
+
+
 def test_vector_kernel_handles_batches_above_16(B):
     M, K, N, group = 37, 512, 136, 128
     case = workloads.make_case(M, K, N, group, seed=5)
