@@ -34,8 +34,13 @@
  * A g_idx entry outside [0, K/group_size) is a precondition violation that the library
  * cannot see without reading device memory; the result is then undefined.
  *
- * Supported shapes: M >= 1; K, N multiples of 8; group_size a multiple of 8 that divides K.
- * Tuned for group_size 128.  All base pointers must be 16-byte aligned.
+ * Supported shapes: M >= 1; K, N multiples of 8; group_size a multiple of 8 that divides K;
+ * K < 2^23, N < 2^24 and K*N < 2^33 (the kernels use 32-bit offsets inside a matrix: packed
+ * weights under 4 GiB).  Tuned for group_size 128.  All base pointers must be 16-byte aligned.
+ *
+ * Format variants.  A checkpoint without zero points (symmetric quantisation) is the same
+ * format with every qzeros word equal to 0x88888888 (z = 8).  Checkpoints that store z - 1
+ * are converted once with gptq_w4a16_shift_zeros().  group_size = K is one group per column.
  */
 #ifndef GPTQ_W4A16_H
 #define GPTQ_W4A16_H
@@ -64,7 +69,7 @@ enum gptq_status {
  * dequantise, stage activations on chip, contract, reduce the split-K partial sums on
  * chip and across workgroups, round once to fp16, store).  `out` is OVERWRITTEN and need
  * not be zeroed (unlike the accumulate-by-atomicAdd contract of Eq. 9-10).
- * By default M = 1 runs the bandwidth-bound split-K vector kernel, 2 <= M <= 32 (up to 64 on layers narrower
+ * By default M = 1 runs the bandwidth-bound split-K vector kernel, 2 <= M <= 32 (up to 48 on layers narrower
  * than 16384 columns) a small-batch MFMA kernel with the same split-K decomposition (when the format allows:
  * no g_idx, group_size % 128 == 0; otherwise the vector kernel up to M = 16), larger M the big-tile fp16
  * MFMA kernel.
@@ -155,6 +160,14 @@ GPTQ_API int gptq_w4a16_plan_query(int M, int K, int N, int group_size, int act_
  */
 GPTQ_API int gptq_w4a16_dequant(const void *qweight, const void *qzeros, const void *scales, const void *g_idx,
                        void *w_out, int K, int N, int group_size, gptq_stream_t stream);
+
+/*
+ * Format conversion, one-time: qzeros_out (int32 [K/group_size, N/8], device; may be qzeros_in) holds
+ * (z + delta) mod 16 for every zero point of qzeros_in.  delta = +1 turns a checkpoint that stores z - 1
+ * (the reading in which a stored 15 stands for z = 0) into the format of this header.
+ */
+GPTQ_API int gptq_w4a16_shift_zeros(const void *qzeros_in, void *qzeros_out, int delta, int K, int N,
+                                    int group_size, gptq_stream_t stream);
 
 /*
  * The unpacked 4-bit fields: q_out (uint8 [K, N], device) = q; z_out (uint8 [K/group_size, N],

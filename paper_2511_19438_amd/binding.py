@@ -34,7 +34,7 @@ class Plan(ctypes.Structure):
 
 
 EXPORTS = ("gptq_w4a16_gemm", "gptq_w4a16_gemm_plan", "gptq_w4a16_plan_query", "gptq_w4a16_act_order_prepare",
-           "gptq_w4a16_gemm_prepared", "gptq_w4a16_dequant", "gptq_w4a16_unpack",
+           "gptq_w4a16_gemm_prepared", "gptq_w4a16_shift_zeros", "gptq_w4a16_dequant", "gptq_w4a16_unpack",
            "gptq_w4a16_workspace_bytes", "gptq_w4a16_set_workspace", "gptq_w4a16_strerror", "gptq_w4a16_version")
 
 
@@ -59,6 +59,8 @@ def load() -> ctypes.CDLL:
     lib.gptq_w4a16_act_order_prepare.restype = ci
     lib.gptq_w4a16_gemm_prepared.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, vp]
     lib.gptq_w4a16_gemm_prepared.restype = ci
+    lib.gptq_w4a16_shift_zeros.argtypes = [vp, vp, ci, ci, ci, ci, vp]
+    lib.gptq_w4a16_shift_zeros.restype = ci
     lib.gptq_w4a16_dequant.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, vp]
     lib.gptq_w4a16_dequant.restype = ci
     lib.gptq_w4a16_unpack.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp]
@@ -165,6 +167,18 @@ def gptq_w4a16_gemm_prepared(x, qweight_sorted, qzeros, scales, perm, out, group
     if rc != 0:
         raise GptqError(rc, "gptq_w4a16_gemm_prepared")
     return out
+
+
+def gptq_w4a16_shift_zeros(qzeros_in, qzeros_out, delta: int, group_size: int):
+    """qzeros_out = (qzeros_in + delta) mod 16 per zero point (one-time format conversion; may be in place)."""
+    G, N8 = qzeros_in.shape
+    if tuple(qzeros_out.shape) != (G, N8):
+        raise ValueError("qzeros_out must have the shape of qzeros_in")
+    rc = load().gptq_w4a16_shift_zeros(_ptr(qzeros_in, torch.int32, "qzeros_in"), _ptr(qzeros_out, torch.int32, "qzeros_out"),
+                                       int(delta), G * int(group_size), N8 * 8, int(group_size), _stream())
+    if rc != 0:
+        raise GptqError(rc, "gptq_w4a16_shift_zeros")
+    return qzeros_out
 
 
 def gptq_w4a16_dequant(qweight, qzeros, scales, g_idx, w_out, group_size: int):

@@ -34,8 +34,10 @@ int check_shape(int K, int N, int group_size)
         return GPTQ_INVALID_ARG;
     if (K % 8 || N % 8 || group_size % 8 || K % group_size)
         return GPTQ_UNSUPPORTED_SHAPE;
-    // element counts must fit the 32-bit index arithmetic of the kernels' row/column numbers
-    if ((long long)K * N > (1LL << 40))
+    // The kernels address with 32-bit byte offsets from 64-bit bases: the packed weights (K*N/2 bytes) must
+    // stay under 4 GiB, a tile's rows of x (256 * K * 2 bytes) too, and row / column numbers under 2^24
+    // (24-bit multiplies).  Real layers are three orders of magnitude below these limits.
+    if (K >= (1 << 23) || N >= (1 << 24) || (long long)K * N >= (1LL << 33))
         return GPTQ_UNSUPPORTED_SHAPE;
     return GPTQ_OK;
 }
@@ -81,18 +83,19 @@ int acquire_workspace(size_t bytes, void **out)
 
 // Default kernel by batch size, from measurement on Llama-shaped layers.  A single row is streamed fastest
 // by the vector kernel.  From two rows on the small-batch MFMA kernel wins: its time is nearly flat up to 16
-// rows and grows slowly to 32, where the vector kernel pays for every weight once per batch row.  The
-// big-tile MFMA kernel needs many tiles to fill the chip; up to 64 rows the small-batch kernel (two launches
-// of 32 rows) is still ahead of it unless the layer is very wide.
+// rows and grows slowly to 32, where the vector kernel pays for every weight once per batch row.  Past 32
+// rows it runs as two launches, which the big-tile MFMA kernel (with K slices on few-tile shapes) beats from
+// about 48 rows on, earlier on very wide layers.
 constexpr int kVectorMaxM = 1;
 constexpr int kSmallBatchAutoMaxM = 32;
+constexpr int kSmallBatchTwoLaunchMaxM = 48;
 constexpr int kSmallBatchTwoLaunchMaxN = 16384;
 
 bool small_batch_by_default(const Problem &p)
 {
     if (!skinny_supported(p))
         return false;
-    return p.M <= kSmallBatchAutoMaxM || (p.M <= kSkinnyMaxM && p.N < kSmallBatchTwoLaunchMaxN);
+    return p.M <= kSmallBatchAutoMaxM || (p.M <= kSmallBatchTwoLaunchMaxM && p.N < kSmallBatchTwoLaunchMaxN);
 }
 
 // What a call resolves to: the kernel and its decomposition, after the automatic choices.
@@ -343,6 +346,23 @@ int gptq_w4a16_gemm_prepared(const void *x, const void *qweight_sorted, const vo
         return GPTQ_HIP_ERROR;
     p.x = xp;
     return launch_resolved(p, r, ws, st);
+}
+
+int gptq_w4a16_shift_zeros(const void *qzeros_in, void *qzeros_out, int delta, int K, int N, int group_size,
+                           gptq_stream_t stream)
+{
+    if (!qzeros_in || !qzeros_out)
+        return GPTQ_INVALID_ARG;
+    const int rc = check_shape(K, N, group_size);
+    if (rc != GPTQ_OK)
+        return rc;
+    if (!aligned16(qzeros_in) || !aligned16(qzeros_out))
+        return GPTQ_MISALIGNED;
+    const long long words = (long long)(K / group_size) * (N / 8);
+    const hipError_t err = launch_shift_zeros(static_cast<const uint32_t *>(qzeros_in),
+                                              static_cast<uint32_t *>(qzeros_out), words, ((delta % 16) + 16) % 16,
+                                              static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
 }
 
 int gptq_w4a16_dequant(const void *qweight, const void *qzeros, const void *scales, const void *g_idx,

@@ -27,6 +27,7 @@ struct Problem {
 // ---- unpack / dequant (standalone, HBM-bound) ----
 hipError_t launch_unpack(const uint32_t *qweight, uint8_t *q_out, const uint32_t *qzeros, uint8_t *z_out, int K,
                          int N, int group_size, hipStream_t stream);
+hipError_t launch_shift_zeros(const uint32_t *in, uint32_t *out, long long words, int delta, hipStream_t stream);
 hipError_t launch_dequant(const uint32_t *qweight, const uint32_t *qzeros, const half_t *scales,
                           const int32_t *g_idx, half_t *w_out, int K, int N, int group_size, hipStream_t stream);
 

@@ -97,6 +97,21 @@ inline unsigned blocks_for(long long items)
     return (unsigned)((items + kThreads - 1) / kThreads);
 }
 
+// z' = (z + delta) mod 16 for every nibble of every word (delta in 0..15; even and odd nibbles apart so that
+// no carry crosses into a neighbour).
+__global__ __launch_bounds__(kThreads) void shift_zeros_kernel(const uint32_t *__restrict__ in,
+                                                               uint32_t *__restrict__ out, long long words,
+                                                               uint32_t delta)
+{
+    const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= words)
+        return;
+    const uint32_t w = in[i];
+    const uint32_t even = ((w & 0x0f0f0f0fu) + delta * 0x01010101u) & 0x0f0f0f0fu;
+    const uint32_t odd = (((w >> 4) & 0x0f0f0f0fu) + delta * 0x01010101u) & 0x0f0f0f0fu;
+    out[i] = even | (odd << 4);
+}
+
 }  // namespace
 
 hipError_t launch_unpack(const uint32_t *qweight, uint8_t *q_out, const uint32_t *qzeros, uint8_t *z_out, int K,
@@ -116,6 +131,13 @@ hipError_t launch_unpack(const uint32_t *qweight, uint8_t *q_out, const uint32_t
         err = hipGetLastError();
     }
     return err;
+}
+
+hipError_t launch_shift_zeros(const uint32_t *in, uint32_t *out, long long words, int delta, hipStream_t stream)
+{
+    hipLaunchKernelGGL(shift_zeros_kernel, dim3(blocks_for(words)), dim3(kThreads), 0, stream, in, out, words,
+                       (uint32_t)(delta & 15));
+    return hipGetLastError();
 }
 
 hipError_t launch_dequant(const uint32_t *qweight, const uint32_t *qzeros, const half_t *scales,

@@ -27,11 +27,11 @@ def declared_functions():
 
 def test_header_declares_the_expected_entry_points():
     names = declared_functions()
-    assert len(names) == len(set(names)) == 11
+    assert len(names) == len(set(names)) == 12
     for required in ("gptq_w4a16_gemm", "gptq_w4a16_dequant", "gptq_w4a16_unpack", "gptq_w4a16_workspace_bytes",
                      "gptq_w4a16_set_workspace", "gptq_w4a16_strerror", "gptq_w4a16_version",
                      "gptq_w4a16_gemm_plan", "gptq_w4a16_plan_query", "gptq_w4a16_act_order_prepare",
-                     "gptq_w4a16_gemm_prepared"):
+                     "gptq_w4a16_gemm_prepared", "gptq_w4a16_shift_zeros"):
         assert required in names
 
 
@@ -110,9 +110,9 @@ def test_default_dispatch_by_batch_size(lib):
     from paper_2511_19438_amd import binding
 
     q = binding.gptq_w4a16_plan_query
-    assert [q(M, 4096, 4096, 128).kernel for M in (1, 2, 3, 16, 32, 33, 64, 65, 2048)] == [1, 3, 3, 3, 3, 3, 3, 2, 2]
+    assert [q(M, 4096, 4096, 128).kernel for M in (1, 2, 3, 16, 32, 33, 48, 49, 2048)] == [1, 3, 3, 3, 3, 3, 3, 2, 2]
     # past 32 rows only layers that are not very wide stay with the small-batch kernel (two launches)
-    assert [q(M, 4096, 22016, 128).kernel for M in (32, 33, 64)] == [3, 2, 2]
+    assert [q(M, 4096, 22016, 128).kernel for M in (32, 33, 48)] == [3, 2, 2]
     # act-order and group sizes the small-batch MFMA kernel does not take fall back
     assert q(8, 4096, 4096, 128, act_order=True).kernel == 1
     assert q(24, 4096, 4096, 128, act_order=True).kernel == 2
@@ -183,3 +183,18 @@ def test_repack_entry_points_validate_before_any_gpu_work(lib):
     assert lib.gptq_w4a16_gemm_prepared(p, p, p, p, p, p, 0, 128, 8, 128, None) == -1
     assert lib.gptq_w4a16_gemm_prepared(p, p, p, p, p, p, 1, 128, 12, 128, None) == -2
     assert lib.gptq_w4a16_gemm_prepared(p, p, odd, p, p, p, 1, 128, 8, 128, None) == -3
+    assert lib.gptq_w4a16_shift_zeros(None, p, 1, 128, 8, 128, None) == -1
+    assert lib.gptq_w4a16_shift_zeros(p, odd, 1, 128, 8, 128, None) == -3
+    assert lib.gptq_w4a16_shift_zeros(p, p, 1, 128, 8, 100, None) == -2
+
+
+def test_shape_limits_of_the_32_bit_offsets(lib):
+    """Matrices whose packed weights would pass 4 GiB (or rows / columns 2^23 / 2^24) are refused, not mis-addressed."""
+    from paper_2511_19438_amd import binding
+
+    for (K, N) in ((1 << 23, 1024), (1024, 1 << 24), (1 << 20, 1 << 13)):
+        with pytest.raises(binding.GptqError) as e:
+            binding.gptq_w4a16_plan_query(1, K, N, 128)
+        assert e.value.code == -2
+        assert lib.gptq_w4a16_workspace_bytes(1, K, N, 128) == 0
+    assert binding.gptq_w4a16_plan_query(1, 1 << 19, 1 << 13, 128).kernel == 1

@@ -464,3 +464,42 @@ def test_repack_refuses_unbalanced_or_out_of_range_groups(B):
     with pytest.raises(B.GptqError) as e:
         B.gptq_w4a16_act_order_prepare(qw, dev(g), qs, perm, group)
     assert e.value.code == -1
+
+
+# ------------------------------------------------------------------ format variants
+
+def test_stored_zero_minus_one_checkpoints_convert_once(B):
+    """A checkpoint that stores z - 1 (mod 16), converted with shift_zeros(+1), gives the canonical tensors'
+    results bit for bit; shifting by -1 afterwards restores the stored words."""
+    M, K, N, group = 4, 1024, 264, 128
+    case = workloads.make_case(M, K, N, group, seed=31)
+    z = oracle.unpack_qzeros(case["qzeros"])
+    stored = oracle.pack_qzeros(((z.astype(np.int32) - 1) % 16).astype(np.uint8))
+    converted = torch.empty_like(dev(stored))
+    B.gptq_w4a16_shift_zeros(dev(stored), converted, 1, group)
+    assert np.array_equal(converted.cpu().numpy().view(np.uint32), case["qzeros"].view(np.uint32))
+    back = dev(stored).clone()
+    B.gptq_w4a16_shift_zeros(converted, back, -1, group)
+    assert np.array_equal(back.cpu().numpy().view(np.uint32), stored.view(np.uint32))
+    B.gptq_w4a16_shift_zeros(back, back, 17, group)   # in place, delta taken mod 16
+    assert np.array_equal(back.cpu().numpy().view(np.uint32), case["qzeros"].view(np.uint32))
+
+
+@pytest.mark.parametrize("M", [1, 8, 300])
+def test_symmetric_checkpoints_are_zero_point_eight(B, M):
+    """No qzeros tensor (symmetric quantisation) = every word 0x88888888."""
+    K, N, group = 1024, 264, 128
+    case = workloads.make_case(M, K, N, group, seed=32)
+    case["qzeros"] = np.full_like(case["qzeros"], np.int32(-2004318072))  # 0x88888888
+    assert np.all(oracle.unpack_qzeros(case["qzeros"]) == 8)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    assert_within_band(run_gemm(B, case, group), ref, f"symmetric M={M}")
+
+
+@pytest.mark.parametrize("M", [1, 8, 300])
+@pytest.mark.parametrize("group", [32, 64, 1024])
+def test_other_group_sizes_including_one_group_per_column(B, M, group):
+    K, N = 1024, 264
+    case = workloads.make_case(M, K, N, group, seed=33 + group)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    assert_within_band(run_gemm(B, case, group), ref, f"group={group} M={M}")
