@@ -88,6 +88,7 @@ GPTQ_API int gptq_w4a16_gemm(const void *x, const void *qweight, const void *qze
 #define GPTQ_ABLATE_SMB 1
 #define GPTQ_ABLATE_VML 2
 #define GPTQ_ABLATE_ILA 4
+#define GPTQ_VECTOR_DOT 8
 
 typedef struct gptq_w4a16_plan {
     int kernel;      /* 0 auto, 1 vector split-K kernel (any M, processed 16 rows at a time), 2 big-tile MFMA kernel,
@@ -109,7 +110,10 @@ typedef struct gptq_w4a16_plan {
                                            not reproducible), one extra launch zeroes the sums;
                         2 GPTQ_ABLATE_VML  activations staged with 16-bit instead of 128-bit loads (Section 3.2);
                         4 GPTQ_ABLATE_ILA  per-weight fp32 conversion and scalar multiply-add instead of packed
-                                           half arithmetic (Section 3.3) */
+                                           half arithmetic (Section 3.3);
+                        and one comparison switch without restrictions on the problem:
+                        8 GPTQ_VECTOR_DOT  contract the packed codes with v_dot2_f32_f16 on the vector ALU instead
+                                           of 4x4x4 MFMAs (the default up to four rows) */
     int reserved[4]; /* must be zero */
 } gptq_w4a16_plan_t;
 

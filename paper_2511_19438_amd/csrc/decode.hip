@@ -85,7 +85,7 @@ void decode_make_plan(const Problem &p, DecodePlan &plan)
     const int gr = p.group_size / 8;
     plan.chunk_rows = act ? 4 : (gr % 4 == 0 ? 4 : (gr % 2 == 0 ? 2 : 1));
     // these variants (and the ablation ones) exist for 64-column tiles only
-    const bool fixed_shape = act || plan.chunk_rows != 4 || plan.flags != 0;
+    const bool fixed_shape = act || plan.chunk_rows != 4 || (plan.flags & 7) != 0;
     const int c = plan.cols_per_wg;
     const bool tile_given = (c == 16 || c == 32 || c == 64 || c == 128 || c == 256) && !fixed_shape;
 

@@ -133,11 +133,19 @@ __device__ __forceinline__ float load_device_scope(const float *p)
 //   kNoIla: every weight is converted to fp32 on its own and multiplied-added with scalar fp32 instructions
 //           instead of packed half conversion and v_dot2_f32_f16 (Section 3.3).
 constexpr int kNoSmb = 1, kNoVml = 2, kNoIla = 4;
+// Not an ablation but a variant of the inner loop, selected with the same parameter: the contraction of the
+// biased codes with the activations goes to the matrix unit (v_mfma_f32_4x4x4_16B_f16: sixteen independent
+// 4x4x4 products per instruction; in each, lane 4b+j supplies row j of A = batch row j and column l of B =
+// this lane's own column, and receives that column of the result) instead of four v_dot2_f32_f16 per packed
+// word: two MFMAs per word that run beside the vector ALU, which is left with the five code-forming
+// operations.  Up to four batch rows ride along for free.
+constexpr int kMatrixDot = 8;
 
 template <int MB, int LPR, int R, bool ACT, int ABL = 0>
 __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
 {
     static_assert(ABL == 0 || (!ACT && MB < 8), "the ablation variants exist for the plain format at small batch");
+    static_assert(!(ABL & kMatrixDot) || MB <= 4, "the 4x4x4 matrix product carries four batch rows");
     constexpr int RL = 64 / LPR;          // row lanes per wavefront
     constexpr int RW = kWaves * RL;       // row lanes per workgroup
     constexpr int CT = LPR * 4;           // columns per workgroup
@@ -323,10 +331,33 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
                             gacc[m][c] = 0.f;
                 }
             }
+            float4_t mdot[4];  // kMatrixDot: per column, the chunk's sums for batch rows 0..3
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                mdot[c] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int rr = 0; rr < R; ++rr) {
                 const uint32_t w[4] = {r.wq[j][rr].x, r.wq[j][rr].y, r.wq[j][rr].z, r.wq[j][rr].w};
                 half2_t d[4][4];
+                if ((ABL & kMatrixDot) && !(ABL & kNoIla)) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        biased_codes(w[c], magic, d[c]);
+                    // A operand: the activations of batch row lane % 4 (rows past MB - 1 repeat it: their results
+                    // are not used), already in the codes' k order (0,4,1,5 | 2,6,3,7)
+                    const int arow = min(lane & 3, MB - 1);
+                    const uint4 xv = *reinterpret_cast<const uint4 *>(xchunk + arow * Ls + rr * 8);
+                    const half4_t a01 = __builtin_bit_cast(half4_t, make_uint2(xv.x, xv.y));
+                    const half4_t a23 = __builtin_bit_cast(half4_t, make_uint2(xv.z, xv.w));
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const half4_t b01 = __builtin_bit_cast(half4_t, make_uint2(as_u32(d[c][0]), as_u32(d[c][1])));
+                        const half4_t b23 = __builtin_bit_cast(half4_t, make_uint2(as_u32(d[c][2]), as_u32(d[c][3])));
+                        mdot[c] = __builtin_amdgcn_mfma_f32_4x4x4f16(a01, b01, mdot[c], 0, 0, 0);
+                        mdot[c] = __builtin_amdgcn_mfma_f32_4x4x4f16(a23, b23, mdot[c], 0, 0, 0);
+                    }
+                    continue;
+                }
                 if (ABL & kNoIla) {
                     // baseline arithmetic: per weight a bit-field extract, an integer-to-float conversion, the
                     // zero point and the scale in fp32, one fp32 multiply-add per batch row
@@ -408,7 +439,8 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
                     const float2 bs = xc[m * nchunks + ul];
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
-                        const float t = __builtin_fmaf(-zf[c], bs.y, gacc[m][c] - bs.x);  // sum_k x_k (q_k - z)
+                        const float dsum = (ABL & kMatrixDot) ? mdot[c][m] : gacc[m][c];
+                        const float t = __builtin_fmaf(-zf[c], bs.y, dsum - bs.x);  // sum_k x_k (q_k - z)
                         acc[m][c] = __builtin_fmaf(sf[c], t, acc[m][c]);
                     }
                 }

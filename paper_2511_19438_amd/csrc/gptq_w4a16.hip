@@ -186,7 +186,7 @@ int check_plan(const gptq_w4a16_plan_t *plan)
     if (plan->kernel < 0 || plan->kernel > 3 || plan->split_k < 0 || plan->tile < 0)
         return GPTQ_INVALID_ARG;
     // the ablation switches belong to the vector kernel
-    if (plan->flags < 0 || plan->flags > 7 || (plan->flags != 0 && plan->kernel != 1))
+    if (plan->flags < 0 || plan->flags > 15 || (plan->flags != 0 && plan->kernel != 1))
         return GPTQ_INVALID_ARG;
     for (int i = 0; i < 4; ++i)
         if (plan->reserved[i] != 0)
@@ -223,7 +223,7 @@ int gptq_w4a16_gemm_plan(const void *x, const void *qweight, const void *qzeros,
     p.K = K;
     p.N = N;
     p.group_size = group_size;
-    if (plan && plan->flags != 0 && !decode_ablation_supported(p))
+    if (plan && (plan->flags & 7) != 0 && !decode_ablation_supported(p))
         return GPTQ_UNSUPPORTED_SHAPE;
     return run_gemm(p, static_cast<hipStream_t>(stream), plan);
 }
@@ -251,7 +251,7 @@ int gptq_w4a16_plan_query(int M, int K, int N, int group_size, int act_order, co
     p.K = K;
     p.N = N;
     p.group_size = group_size;
-    if (request && request->flags != 0 && !decode_ablation_supported(p))
+    if (request && (request->flags & 7) != 0 && !decode_ablation_supported(p))
         return GPTQ_UNSUPPORTED_SHAPE;
     const Resolved r = resolve(p, request);
     gptq_w4a16_plan_t out = {};

@@ -81,7 +81,7 @@ def test_plan_validation(lib):
     bad = binding.Plan(kernel=4)
     assert lib.gptq_w4a16_gemm_plan(p, p, p, p, None, p, 1, 128, 8, 128, None, ctypes.byref(bad)) == -1
     # the ablation switches belong to the vector kernel, have three bits and exist for small plain problems
-    for bad in (binding.Plan(flags=1), binding.Plan(kernel=2, flags=1), binding.Plan(kernel=1, flags=8),
+    for bad in (binding.Plan(flags=1), binding.Plan(kernel=2, flags=1), binding.Plan(kernel=1, flags=16),
                 binding.Plan(kernel=1, flags=-1)):
         assert lib.gptq_w4a16_gemm_plan(p, p, p, p, None, p, 1, 128, 8, 128, None, ctypes.byref(bad)) == -1
     ok = binding.Plan(kernel=1, flags=5)

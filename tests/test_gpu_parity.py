@@ -164,8 +164,8 @@ def test_decode_deep_slices(B, M, K, split_k):
         assert_within_band(out, ref, f"deep slice M={M} K={K} tile={tile}")
 
 
-@pytest.mark.parametrize("flags", [1, 2, 3, 4, 5, 6, 7])
-@pytest.mark.parametrize("M,split_k", [(1, 0), (1, 3), (3, 1), (4, 2)])
+@pytest.mark.parametrize("flags", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("M,split_k", [(1, 0), (1, 3), (2, 0), (3, 1), (4, 2)])
 def test_ablation_variants_match_oracle(B, flags, M, split_k):
     """Each of the paper's three techniques taken out in turn (and together): the baselines they replace
     compute the same result, inside the same band (the atomic commit adds in no fixed order)."""
