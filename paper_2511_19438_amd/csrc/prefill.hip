@@ -31,10 +31,10 @@ struct TileShape {
 };
 // ids 1..10, see the plan documentation in the public header
 constexpr TileShape kTiles[11] = {
-    {0, 0, 64, 0.0, 1.0, false},      {256, 256, 64, 0.0, 1.0, false},  {256, 128, 64, 0.0, 1.0, false},
+    {0, 0, 64, 0.0, 1.0, false},      {256, 256, 64, 1.25, 1.0, false}, {256, 128, 64, 0.0, 1.0, false},
     {128, 128, 64, 0.85, 1.1, true},  {128, 256, 64, 0.0, 1.0, false},  {64, 128, 64, 0.455, 1.3, true},
     {32, 256, 64, 0.75, 1.3, false},  {256, 256, 32, 0.0, 1.0, false},  {128, 256, 64, 0.99, 1.0, false},
-    {256, 256, 64, 1.47, 1.0, false}, {256, 256, 32, 0.0, 1.0, false}};
+    {256, 256, 64, 1.40, 1.0, false}, {256, 256, 32, 0.0, 1.0, false}};
 constexpr int kNumTiles = 10;
 constexpr int kComputeUnits = 256;
 constexpr size_t kCounterBytes = 256 * 1024;  // same fixed counter area as the other kernels

@@ -106,6 +106,21 @@ __device__ __forceinline__ uint32_t dequant_pair(uint32_t w, const PairMagic &k,
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// The same in two halves, so that independent work can sit between the add and the multiply (a packed
+// multiply that consumes the result of the packed add right before it costs a wait state).
+template <int P>
+__device__ __forceinline__ uint32_t dequant_pair_begin(uint32_t w, const PairMagic &k, uint32_t nz)
+{
+    const uint32_t spread = __builtin_amdgcn_perm(0u, w, 0x0c000c00u | P | (P << 16));
+    const half2_t v = as_half2((spread & k.mask) | k.bias) + as_half2(nz);
+    return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ uint32_t dequant_pair_end(uint32_t diff, uint32_t ss)
+{
+    const half2_t v = as_half2(diff) * as_half2(ss);
+    return __builtin_bit_cast(uint32_t, v);
+}
+
 __device__ __forceinline__ u32x4_t dequant_word(uint32_t w, const PairMagic &k, const uint32_t nz[4],
                                                 const uint32_t ss[4])
 {
@@ -312,10 +327,45 @@ __global__ __launch_bounds__(kThreads) void prefill_pipelined_kernel(const Args 
     uint32_t nz_cur[TN], ss_cur[TN], nz_nxt[TN], ss_nxt[TN];
     const PairMagic magic;
 
+    // A operand of 32-row block i at k step kk: row wm*WAVE_M + 32 i + lj, chunk (2 kk + kh) ^ swizzle(row).
+    // The swizzle does not depend on i (32 rows are a whole number of swizzle periods), so the byte offset is
+    // a per-lane value per k step plus i * 32 rows: the reads of one k step share ONE address register (the
+    // stage buffer's base added once per k step) and differ in the instruction's immediate offset.
+    uint32_t a_lane_off[KSTEPS];
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+        const int row = wm * WAVE_M + lj;
+        a_lane_off[kk] = (uint32_t)(row * (BK * 2) + (((2 * kk + kh) ^ ((row / RPB) & (CH - 1))) * 16));
+    }
+    // The reads are issued as inline asm and waited for by hand (`wait_afrag`): the compiler's own counter
+    // bookkeeping loses track of the order of LDS operations across the loop's back edge and falls back to
+    // waiting for ALL outstanding LDS reads - including the one issued a few cycles earlier - before the first
+    // use of every operand, which stalls the matrix pipe for an LDS round trip several times per k step.
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     auto read_afrag = [&](int ring, int kk, int i, half8_t &dst) {
-        const int row = wm * WAVE_M + i * 32 + lj;
-        const int ch = (2 * kk + kh) ^ ((row / RPB) & (CH - 1));
-        dst = *reinterpret_cast<const half8_t *>(stage_base(ring) + (size_t)row * (BK * 2) + ch * 16);
+        const uint32_t addr = smem_base + a_lane_off[kk] + (uint32_t)ring * (uint32_t)L::BYTES;
+#define GPTQ_READ_A(I) \
+    case I: asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"((I) * 32 * BK * 2)); break;
+        switch (i) {  // (the immediate offset must be a constant expression: one case per 32-row block)
+            GPTQ_READ_A(0) GPTQ_READ_A(1) GPTQ_READ_A(2) GPTQ_READ_A(3)
+            GPTQ_READ_A(4) GPTQ_READ_A(5) GPTQ_READ_A(6) GPTQ_READ_A(7)
+        }
+#undef GPTQ_READ_A
+    };
+    // Before the first use of operand i of a k step: LDS reads return in order, and the reads issued after
+    // operand i's are the rest of its own k step (TM-1-i) and those of the current k step issued so far
+    // (one per slot in the first TM slots).  Reads the compiler issues in between only make this stricter.
+    // (The operand is an in/out of the wait, so that the MFMA that consumes it cannot be moved above it.)
+    auto wait_afrag = [&](int i, half8_t &frag) {
+#define GPTQ_WAIT_A(I)                                                                                              \
+    case I:                                                                                                         \
+        asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(frag) : "n"(TM - 1 - (I) + (((I) * TN < TM) ? (I) * TN : TM))); \
+        break;
+        switch (i) {
+            GPTQ_WAIT_A(0) GPTQ_WAIT_A(1) GPTQ_WAIT_A(2) GPTQ_WAIT_A(3)
+            GPTQ_WAIT_A(4) GPTQ_WAIT_A(5) GPTQ_WAIT_A(6) GPTQ_WAIT_A(7)
+        }
+#undef GPTQ_WAIT_A
     };
     // this lane's packed words, scales and zero points of a whole stage
     auto read_weights = [&](int ring, uint32_t (&w)[KSTEPS][TN], uint32_t (&nz)[TN], uint32_t (&ss)[TN]) {
@@ -358,25 +408,49 @@ __global__ __launch_bounds__(kThreads) void prefill_pipelined_kernel(const Args 
     auto kstep = [&](auto parity, int next_ring, int next_kk, const uint32_t (&nw)[TN], const uint32_t (&nnz)[TN],
                      const uint32_t (&nss)[TN], auto &&extra) {
         constexpr int CUR = std::decay_t<decltype(parity)>::value, NXT = CUR ^ 1;
+        uint32_t pending[(PAIRS + SLOTS - 1) / SLOTS] = {};
 #pragma unroll
         for (int m = 0; m < SLOTS; ++m) {
             const int i = m / TN, t = m % TN;
+            if (t == 0)
+                wait_afrag(i, afr[CUR][i]);
             acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr[CUR][i], __builtin_bit_cast(half8_t, bfr[CUR][t]),
                                                                acc[i][t], 0, 0, 0);
             if (m < TM)
                 read_afrag(next_ring, next_kk, m, afr[NXT][m]);
-            // pairs [m * PAIRS / SLOTS, (m + 1) * PAIRS / SLOTS) belong to this slot
+            // pairs [m * PAIRS / SLOTS, (m + 1) * PAIRS / SLOTS) belong to this slot: their conversion and
+            // zero-point subtraction happen here, the multiply by the scale one slot later (the last slot
+            // finishes its own), so no multiply directly follows the add it depends on
+            constexpr int PPS = (PAIRS + SLOTS - 1) / SLOTS;
+            uint32_t now[PPS];
 #pragma unroll
             for (int pair = m * PAIRS / SLOTS; pair < (m + 1) * PAIRS / SLOTS; ++pair) {
                 const int pt = pair >> 2;
                 uint32_t r;
                 switch (pair & 3) {
-                case 0: r = dequant_pair<0>(nw[pt], magic, nnz[pt], nss[pt]); break;
-                case 1: r = dequant_pair<1>(nw[pt], magic, nnz[pt], nss[pt]); break;
-                case 2: r = dequant_pair<2>(nw[pt], magic, nnz[pt], nss[pt]); break;
-                default: r = dequant_pair<3>(nw[pt], magic, nnz[pt], nss[pt]); break;
+                case 0: r = dequant_pair_begin<0>(nw[pt], magic, nnz[pt]); break;
+                case 1: r = dequant_pair_begin<1>(nw[pt], magic, nnz[pt]); break;
+                case 2: r = dequant_pair_begin<2>(nw[pt], magic, nnz[pt]); break;
+                default: r = dequant_pair_begin<3>(nw[pt], magic, nnz[pt]); break;
                 }
-                bfr[NXT][pt][pair & 3] = r;
+                now[pair - m * PAIRS / SLOTS] = r;
+            }
+            if (m > 0) {
+#pragma unroll
+                for (int pair = (m - 1) * PAIRS / SLOTS; pair < m * PAIRS / SLOTS; ++pair) {
+                    const int pt = pair >> 2;
+                    bfr[NXT][pt][pair & 3] = dequant_pair_end(pending[pair - (m - 1) * PAIRS / SLOTS], nss[pt]);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < PPS; ++q)
+                pending[q] = now[q];
+            if (m == SLOTS - 1) {
+#pragma unroll
+                for (int pair = m * PAIRS / SLOTS; pair < (m + 1) * PAIRS / SLOTS; ++pair) {
+                    const int pt = pair >> 2;
+                    bfr[NXT][pt][pair & 3] = dequant_pair_end(pending[pair - m * PAIRS / SLOTS], nss[pt]);
+                }
             }
             extra(m);
             __builtin_amdgcn_sched_barrier(0);

@@ -44,11 +44,11 @@ def device_weights(K, N, seed, act_order=False):
     return _weights_cache[key]
 
 
-def check_sampled(B, M, K, N, seed, act_order=False, tight=0.25):
+def check_sampled(B, M, K, N, seed, act_order=False, tight=0.25, plan=None):
     w, d = device_weights(K, N, seed, act_order)
     x = workloads.make_activations(M, K, seed=seed)
     out = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
-    B.gptq_w4a16_gemm(torch.from_numpy(x).cuda(), d["qweight"], d["qzeros"], d["scales"], d["g_idx"], out, GROUP)
+    B.gptq_w4a16_gemm(torch.from_numpy(x).cuda(), d["qweight"], d["qzeros"], d["scales"], d["g_idx"], out, GROUP, plan)
     torch.cuda.synchronize()
     got = out.cpu().numpy()
     assert np.all(np.isfinite(got)), "non-finite output"
@@ -118,3 +118,11 @@ def test_dequant_full_size_70b_down_projection_is_bit_exact_on_samples(B):
         g = k0 // GROUP
         expect = oracle.dequant(w["qweight"][rows], w["qzeros"][g:g + 1], w["scales"][g:g + 1], None, GROUP)
         assert np.array_equal(got[k0:k0 + GROUP], expect.view(np.uint16))
+
+
+@pytest.mark.parametrize("tile,split_k", [(5, 1), (5, 4), (3, 1), (3, 2), (6, 1), (8, 1), (1, 1), (9, 1)])
+def test_big_tile_kernel_with_several_workgroups_per_compute_unit(B, tile, split_k):
+    """Enough workgroups of every tile shape that several share a compute unit (small tiles: up to 1024 of them):
+    LDS latencies are then longer than when a workgroup runs alone, which is what the hand-placed waits of the
+    pipelined kernel must cover."""
+    check_sampled(B, 512, 2048, 4096, seed=4242, plan=B.Plan(kernel=2, tile=tile, split_k=split_k))
