@@ -139,8 +139,9 @@ GPTQ_API int gptq_w4a16_act_order_prepare(const void *qweight, const void *g_idx
 /*
  * The act-order GEMM on a repacked checkpoint:  out[m, n] = sum_j x[m, perm[j]] * W_sorted[j, n],
  * equal (up to the order of the fp32 additions) to gptq_w4a16_gemm with the original qweight and
- * g_idx.  x is gathered into scratch (M*K fp16) and the kernels of the plain format run on it;
- * otherwise the contract of gptq_w4a16_gemm.  A caller-owned workspace must hold
+ * g_idx.  At M = 1 the vector kernel gathers x through perm while it stages it (one launch; perm
+ * entries outside [0, K) read x[K-1]); for larger M x is first gathered into scratch (M*K fp16) and
+ * the kernels of the plain format run on it; otherwise the contract of gptq_w4a16_gemm.  A caller-owned workspace must hold
  * gptq_w4a16_workspace_bytes(M, K, N, group_size) + 256 + 2*M*K bytes.
  */
 GPTQ_API int gptq_w4a16_gemm_prepared(const void *x, const void *qweight_sorted, const void *qzeros,

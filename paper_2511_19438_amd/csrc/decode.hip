@@ -199,6 +199,7 @@ hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspa
         a.qzeros = p.qzeros;
         a.scales = p.scales;
         a.g_idx = p.g_idx;
+        a.x_perm = p.x_perm;
         a.out = p.out + (size_t)m0 * p.N;
         a.counters = reinterpret_cast<unsigned *>(ws);
         a.partial = reinterpret_cast<float *>(ws + decode_counter_bytes(p.N));
@@ -240,13 +241,14 @@ hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspa
             if (hipGetLastError() != hipSuccess)
                 return hipErrorLaunchFailure;
         }
+        const int flags = plan.flags | (p.x_perm ? decode::kGatherX : 0);
         hipError_t err;
         switch (mb) {
-        case 1: err = decode::launch_mb<1>(a, d.lpr, plan.chunk_rows, act, plan.flags, lds, stream); break;
-        case 2: err = decode::launch_mb<2>(a, d.lpr, plan.chunk_rows, act, plan.flags, lds, stream); break;
-        case 4: err = decode::launch_mb<4>(a, d.lpr, plan.chunk_rows, act, plan.flags, lds, stream); break;
-        case 8: err = decode::launch_mb<8>(a, d.lpr, plan.chunk_rows, act, plan.flags, lds, stream); break;
-        default: err = decode::launch_mb<16>(a, d.lpr, plan.chunk_rows, act, plan.flags, lds, stream); break;
+        case 1: err = decode::launch_mb<1>(a, d.lpr, plan.chunk_rows, act, flags, lds, stream); break;
+        case 2: err = decode::launch_mb<2>(a, d.lpr, plan.chunk_rows, act, flags, lds, stream); break;
+        case 4: err = decode::launch_mb<4>(a, d.lpr, plan.chunk_rows, act, flags, lds, stream); break;
+        case 8: err = decode::launch_mb<8>(a, d.lpr, plan.chunk_rows, act, flags, lds, stream); break;
+        default: err = decode::launch_mb<16>(a, d.lpr, plan.chunk_rows, act, flags, lds, stream); break;
         }
         if (err != hipSuccess)
             return err;

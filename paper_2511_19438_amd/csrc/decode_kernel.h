@@ -35,6 +35,7 @@ struct Args {
     const uint32_t *qzeros;
     const half_t *scales;
     const int32_t *g_idx;
+    const int32_t *x_perm;  // [K] source position of each activation element (kGatherX), else unused
     half_t *out;
     float *partial;       // [split_k, M, N] fp32, only if split_k > 1
     unsigned *counters;   // [tiles_n], zero between launches
@@ -140,6 +141,9 @@ constexpr int kNoSmb = 1, kNoVml = 2, kNoIla = 4;
 // word: two MFMAs per word that run beside the vector ALU, which is left with the five code-forming
 // operations.  Up to four batch rows ride along for free.
 constexpr int kMatrixDot = 8;
+// Another variant: the activations are gathered through Args::x_perm while they are staged (the weight's rows
+// were sorted by group once, so that it reads like the plain format; the activations follow them per call).
+constexpr int kGatherX = 16;
 
 template <int MB, int LPR, int R, bool ACT, int ABL = 0>
 __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
@@ -233,6 +237,17 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
     auto x_load = [&](int i) -> half8_t {
         const int m = MB == 1 ? 0 : i / rows_p;
         const int row = i - m * rows_p;
+        if (ABL & kGatherX) {  // the activations of a row-sorted weight: element k comes from position x_perm[k]
+            const int32_t *ps = a.x_perm + kbeg + min(row, rows_s - 1) * 8;
+            const int4 pa = *reinterpret_cast<const int4 *>(ps);
+            const int4 pb = *reinterpret_cast<const int4 *>(ps + 4);
+            const half_t *xr = a.x + (size_t)min(m, a.M - 1) * a.K;
+            const unsigned last = (unsigned)a.K - 1u;  // a position outside the row reads its last element
+            return half8_t{xr[min((unsigned)pa.x, last)], xr[min((unsigned)pa.y, last)],
+                           xr[min((unsigned)pa.z, last)], xr[min((unsigned)pa.w, last)],
+                           xr[min((unsigned)pb.x, last)], xr[min((unsigned)pb.y, last)],
+                           xr[min((unsigned)pb.z, last)], xr[min((unsigned)pb.w, last)]};
+        }
         const half_t *src = a.x + (size_t)min(m, a.M - 1) * a.K + kbeg + min(row, rows_s - 1) * 8;
         if (ABL & kNoVml) {  // eight separate 16-bit loads (volatile: not to be merged)
             const volatile half_t *v = src;

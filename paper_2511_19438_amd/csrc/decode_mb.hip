@@ -34,6 +34,20 @@ hipError_t launch_mb<GPTQ_DECODE_MB>(const Args &a, int lpr, int chunk_rows, boo
     constexpr int MB = GPTQ_DECODE_MB;
     // The inner loop of the plain format with chunks of four packed rows, up to four batch rows, contracts on
     // the matrix unit (kMatrixDot); measured 3-6 % faster than v_dot2_f32_f16 at M = 1.
+#if GPTQ_DECODE_MB == 1
+    if (ablate & kGatherX) {  // activations gathered while staged: the default inner loop only
+        if (ablate != kGatherX || act || chunk_rows != 4)
+            return hipErrorInvalidValue;
+        switch (lpr) {
+        case 4: return launch_one<MB, 4, 4, false, kMatrixDot | kGatherX>(a, lds_bytes, stream);
+        case 8: return launch_one<MB, 8, 4, false, kMatrixDot | kGatherX>(a, lds_bytes, stream);
+        case 16: return launch_one<MB, 16, 4, false, kMatrixDot | kGatherX>(a, lds_bytes, stream);
+        case 32: return launch_one<MB, 32, 4, false, kMatrixDot | kGatherX>(a, lds_bytes, stream);
+        case 64: return launch_one<MB, 64, 4, false, kMatrixDot | kGatherX>(a, lds_bytes, stream);
+        default: return hipErrorInvalidValue;
+        }
+    }
+#endif
 #if GPTQ_DECODE_MB <= 4
     const bool vector_dot = (ablate & 8) != 0;  // comparison switch: keep the v_dot2_f32_f16 loop
     ablate &= 7;
@@ -48,6 +62,8 @@ hipError_t launch_mb<GPTQ_DECODE_MB>(const Args &a, int lpr, int chunk_rows, boo
         }
     }
 #endif
+    if (ablate & kGatherX)
+        return hipErrorInvalidValue;
     if (ablate != 0) {
         // the ablation variants exist for the default tile shape of the plain format, up to four rows; taking
         // the packed arithmetic out (kNoIla) replaces the whole inner loop, the other two keep the matrix-unit one

@@ -330,6 +330,20 @@ int gptq_w4a16_gemm_prepared(const void *x, const void *qweight_sorted, const vo
     p.N = N;
     p.group_size = group_size;
     const Resolved r = resolve(p, nullptr);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (r.kernel == 1 && M == 1 && r.decode.chunk_rows == 4 && r.decode.flags == 0) {
+        // the vector kernel gathers the activations itself while it stages them: one launch
+        p.x = static_cast<const half_t *>(x);
+        p.x_perm = static_cast<const int32_t *>(perm);
+        void *ws = nullptr;
+        const size_t bytes = scratch_bytes(p, r);
+        if (bytes > 0) {
+            const int wrc = acquire_workspace(bytes, &ws);
+            if (wrc != GPTQ_OK)
+                return wrc;
+        }
+        return launch_resolved(p, r, ws, st);
+    }
     // scratch: what the kernel needs, then the gathered activations
     // (the counter area at the front stays reserved even if this launch needs none: it must remain zero)
     size_t kernel_bytes = align256(scratch_bytes(p, r));
@@ -340,7 +354,6 @@ int gptq_w4a16_gemm_prepared(const void *x, const void *qweight_sorted, const vo
     if (wrc != GPTQ_OK)
         return wrc;
     half_t *xp = reinterpret_cast<half_t *>(static_cast<unsigned char *>(ws) + kernel_bytes);
-    hipStream_t st = static_cast<hipStream_t>(stream);
     if (launch_gather_activations(static_cast<const half_t *>(x), static_cast<const int32_t *>(perm), xp, M, K, st) !=
         hipSuccess)
         return GPTQ_HIP_ERROR;

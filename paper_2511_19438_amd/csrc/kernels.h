@@ -20,6 +20,7 @@ struct Problem {
     const uint32_t *qzeros;   // [K/group, N/8]
     const half_t *scales;     // [K/group, N]
     const int32_t *g_idx;     // [K] or nullptr
+    const int32_t *x_perm = nullptr;  // [K]: gather x through it while staging (vector kernel, M = 1 only)
     half_t *out;              // [M, N]
     int M, K, N, group_size;
 };
