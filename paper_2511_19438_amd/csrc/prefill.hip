@@ -28,13 +28,17 @@ struct TileShape {
     double overlap;   // how many workgroups' worth of work a compute unit does in one workgroup's time when
                       // several are resident (small tiles: their pipelines interleave); 1 = one at a time
     bool may_split;   // K slices pay only where a thread holds few accumulators (the combine moves them all)
+    double pair_us;   // if > 0: exactly two workgroups fit a compute unit and a stage takes this long when two
+                      // are resident (they share the matrix pipe); the estimate then counts waves of 512
 };
 // ids 1..10, see the plan documentation in the public header
 constexpr TileShape kTiles[11] = {
-    {0, 0, 64, 0.0, 1.0, false},      {256, 256, 64, 1.25, 1.0, false}, {256, 128, 64, 0.0, 1.0, false},
-    {128, 128, 64, 0.85, 1.1, true},  {128, 256, 64, 0.0, 1.0, false},  {64, 128, 64, 0.455, 1.3, true},
-    {32, 256, 64, 0.75, 1.3, false},  {256, 256, 32, 0.0, 1.0, false},  {128, 256, 64, 0.99, 1.0, false},
-    {256, 256, 64, 1.40, 1.0, false}, {256, 256, 32, 0.0, 1.0, false}};
+    {0, 0, 64, 0.0, 1.0, false, 0.0},      {256, 256, 64, 1.25, 1.0, false, 0.0},
+    {256, 128, 64, 0.0, 1.0, false, 0.0},  {128, 128, 64, 0.85, 1.1, true, 0.0},
+    {128, 256, 64, 0.0, 1.0, false, 0.0},  {64, 128, 64, 0.455, 1.3, true, 0.0},
+    {32, 256, 64, 0.75, 1.3, false, 0.0},  {256, 256, 32, 0.0, 1.0, false, 0.0},
+    {128, 256, 64, 0.99, 1.0, false, 1.31}, {256, 256, 64, 1.40, 1.0, false, 0.0},
+    {256, 256, 32, 0.0, 1.0, false, 0.0}};
 constexpr int kNumTiles = 10;
 constexpr int kComputeUnits = 256;
 constexpr size_t kCounterBytes = 256 * 1024;  // same fixed counter area as the other kernels
@@ -57,6 +61,16 @@ double estimate_us(const Problem &p, int t, int split)
     const int sps = ceil_div_i(stages, split);
     const int slices = ceil_div_i(stages, sps);
     const double wgs = (double)tiles * slices;
+    if (ts.pair_us > 0.0) {
+        // whole waves of two workgroups per compute unit, then the rest: alone if it fits one per unit
+        const int per_wave = 2 * kComputeUnits;
+        const int waves = (int)wgs / per_wave;
+        const int rest = (int)wgs - waves * per_wave;
+        double us = 3.5 + waves * (sps * ts.pair_us + 1.5) + (slices > 1 ? 5.0 : 0.0);
+        if (rest > 0)
+            us += sps * (rest > kComputeUnits ? ts.pair_us : ts.stage_us) + 1.5;
+        return us;
+    }
     double rounds = ts.overlap > 1.0 ? wgs / (kComputeUnits * ts.overlap) : std::ceil(wgs / kComputeUnits);
     if (rounds < 1.0)
         rounds = 1.0;

@@ -193,8 +193,13 @@ struct StageLayout {
     static constexpr int BYTES = A_BYTES + B_BYTES + SZ_BYTES;
 };
 
+// Tiles with up to 128 accumulator registers per lane are compiled to fit two workgroups on a compute unit
+// (256 registers per lane each): one workgroup's dequantisation then runs under the other's MFMAs.
+template <int BM, int BN>
+constexpr int kWavesPerSimd = (BM * BN <= 128 * 256) ? 2 : 1;
+
 template <int BM, int BN, int WM, int WN, int BK, int NBUF>
-__global__ __launch_bounds__(kThreads) void prefill_pipelined_kernel(const Args a)
+__global__ __launch_bounds__(kThreads, (kWavesPerSimd<BM, BN>)) void prefill_pipelined_kernel(const Args a)
 {
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
     static_assert(BK == 32 || BK == 64, "stage of 32 or 64 k");
