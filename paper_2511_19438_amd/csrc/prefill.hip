@@ -18,6 +18,8 @@ template <> hipError_t launch_tile<7>(const Args &, int, hipStream_t);
 template <> hipError_t launch_tile<8>(const Args &, int, hipStream_t);
 template <> hipError_t launch_tile<9>(const Args &, int, hipStream_t);
 template <> hipError_t launch_tile<10>(const Args &, int, hipStream_t);
+template <> hipError_t launch_tile<11>(const Args &, int, hipStream_t);
+template <> hipError_t launch_tile<12>(const Args &, int, hipStream_t);
 }  // namespace prefill
 
 namespace {
@@ -32,14 +34,15 @@ struct TileShape {
                       // are resident (they share the matrix pipe); the estimate then counts waves of 512
 };
 // ids 1..10, see the plan documentation in the public header
-constexpr TileShape kTiles[11] = {
+constexpr TileShape kTiles[13] = {
     {0, 0, 64, 0.0, 1.0, false, 0.0},      {256, 256, 64, 1.25, 1.0, false, 0.0},
     {256, 128, 64, 0.0, 1.0, false, 0.0},  {128, 128, 64, 0.85, 1.1, true, 0.0},
     {128, 256, 64, 0.0, 1.0, false, 0.0},  {64, 128, 64, 0.455, 1.3, true, 0.0},
     {32, 256, 64, 0.75, 1.3, false, 0.0},  {256, 256, 32, 0.0, 1.0, false, 0.0},
     {128, 256, 64, 0.99, 1.0, false, 1.31}, {256, 256, 64, 1.40, 1.0, false, 0.0},
-    {256, 256, 32, 0.0, 1.0, false, 0.0}};
-constexpr int kNumTiles = 10;
+    {256, 256, 32, 0.0, 1.0, false, 0.0},   {64, 128, 64, 0.0, 1.0, true, 0.0},
+    {32, 128, 64, 0.0, 1.0, true, 0.0}};
+constexpr int kNumTiles = 12;
 constexpr int kComputeUnits = 256;
 constexpr size_t kCounterBytes = 256 * 1024;  // same fixed counter area as the other kernels
 constexpr int kMaxSplit = 32;
@@ -185,6 +188,8 @@ hipError_t launch_prefill(const Problem &p, const PrefillPlan &plan, void *works
     case 8: return prefill::launch_tile<8>(a, mode, stream);
     case 9: return prefill::launch_tile<9>(a, mode, stream);
     case 10: return prefill::launch_tile<10>(a, mode, stream);
+    case 11: return prefill::launch_tile<11>(a, mode, stream);
+    case 12: return prefill::launch_tile<12>(a, mode, stream);
     default: return hipErrorInvalidValue;
     }
 }

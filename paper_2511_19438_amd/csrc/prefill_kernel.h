@@ -532,8 +532,14 @@ __global__ __launch_bounds__(kThreads, (kWavesPerSimd<BM, BN>)) void prefill_pip
         publish();  // stage s+2 has landed; everyone is done with stage s
         ring = ring_next;
     }
-    // nothing may still be writing this workgroup's LDS when it retires
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // nothing may still be writing this workgroup's LDS when it retires; the LDS wait retires the operand reads
+    // issued for the stage after the last one, whose destination registers stay reserved until here (named as
+    // in/outs after the wait: the compiler knows nothing of the inline-asm reads in flight and could otherwise
+    // reuse the registers of these dead values while a read is still due to land in them)
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+        asm volatile("" : "+v"(afr[0][i]), "+v"(afr[1][i]));
 
     if (a.split_k > 1) {
         // ---- combine the K slices: every slice leaves its accumulators in scratch (element e of thread t at
