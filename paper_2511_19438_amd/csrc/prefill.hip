@@ -18,31 +18,39 @@ template <> hipError_t launch_tile<7>(const Args &, int, hipStream_t);
 template <> hipError_t launch_tile<8>(const Args &, int, hipStream_t);
 template <> hipError_t launch_tile<9>(const Args &, int, hipStream_t);
 template <> hipError_t launch_tile<10>(const Args &, int, hipStream_t);
-template <> hipError_t launch_tile<11>(const Args &, int, hipStream_t);
-template <> hipError_t launch_tile<12>(const Args &, int, hipStream_t);
 }  // namespace prefill
 
 namespace {
 
 struct TileShape {
     int bm, bn, bk;
-    double stage_us;  // one 64-k stage of a workgroup of this tile, measured (0 = tile is never auto-selected)
-    double overlap;   // how many workgroups' worth of work a compute unit does in one workgroup's time when
-                      // several are resident (small tiles: their pipelines interleave); 1 = one at a time
+    double stage_us;  // one 64-k stage of a workgroup that has a compute unit to itself, measured
+                      // (0 = tile is never auto-selected)
     bool may_split;   // K slices pay only where a thread holds few accumulators (the combine moves them all)
-    double pair_us;   // if > 0: exactly two workgroups fit a compute unit and a stage takes this long when two
-                      // are resident (they share the matrix pipe); the estimate then counts waves of 512
+    double pair_us;   // big tiles, if > 0: exactly two workgroups fit a compute unit and a stage takes this long
+                      // when two are resident (they share the matrix pipe); the estimate counts waves of 512
+    // small tiles (resident > 0): up to `resident` workgroups share a compute unit and a stage of each takes
+    // pace[r-1] with r of them resident; fixed_us covers launch, pipeline fill and the store; a split moves
+    // every slice's partial tile through scratch once each way at scratch_tbps
+    int resident;
+    double pace[3];
+    double fixed_us;
+    double scratch_tbps;
 };
 // ids 1..10, see the plan documentation in the public header
-constexpr TileShape kTiles[13] = {
-    {0, 0, 64, 0.0, 1.0, false, 0.0},      {256, 256, 64, 1.25, 1.0, false, 0.0},
-    {256, 128, 64, 0.0, 1.0, false, 0.0},  {128, 128, 64, 0.85, 1.1, true, 0.0},
-    {128, 256, 64, 0.0, 1.0, false, 0.0},  {64, 128, 64, 0.455, 1.3, true, 0.0},
-    {32, 256, 64, 0.75, 1.3, false, 0.0},  {256, 256, 32, 0.0, 1.0, false, 0.0},
-    {128, 256, 64, 0.99, 1.0, false, 1.31}, {256, 256, 64, 1.40, 1.0, false, 0.0},
-    {256, 256, 32, 0.0, 1.0, false, 0.0},   {64, 128, 64, 0.0, 1.0, true, 0.0},
-    {32, 128, 64, 0.0, 1.0, true, 0.0}};
-constexpr int kNumTiles = 12;
+constexpr TileShape kTiles[11] = {
+    {0, 0, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
+    {256, 256, 64, 1.25, false, 0.0, 0, {0, 0, 0}, 0, 0},
+    {256, 128, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
+    {128, 128, 64, 0.75, true, 0.0, 2, {0.75, 1.4, 0}, 7.0, 6.0},
+    {128, 256, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
+    {64, 128, 64, 0.46, true, 0.0, 3, {0.46, 0.72, 1.0}, 6.0, 6.0},
+    {32, 256, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
+    {256, 256, 32, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
+    {128, 256, 64, 0.99, false, 1.31, 0, {0, 0, 0}, 0, 0},
+    {256, 256, 64, 1.40, false, 0.0, 0, {0, 0, 0}, 0, 0},
+    {256, 256, 32, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0}};
+constexpr int kNumTiles = 10;
 constexpr int kComputeUnits = 256;
 constexpr size_t kCounterBytes = 256 * 1024;  // same fixed counter area as the other kernels
 constexpr int kMaxSplit = 32;
@@ -53,9 +61,11 @@ int ceil_div_i(int a, int b)
 }
 
 // Estimated duration (microseconds) of the pipelined kernel with tile `t` and `split` K slices.  A workgroup
-// walks its stages at a fixed pace (the pipeline is latency bound when it has a compute unit to itself, and
-// co-resident workgroups share the matrix pipe), so the chip needs ceil(workgroups / 256) such walks; a split
-// adds the scratch round trip of the combine.  Stage times measured on Llama-7B shapes, M = 48 ... 2048.
+// walks its stages at a pace set by instruction issue and latency, not by the matrix pipe or by HBM: alone on
+// a compute unit it leaves most of it idle, and co-resident workgroups slow each other down by less than their
+// number.  Big tiles: whole rounds (or waves of pairs) of workgroups.  Small tiles: workgroups per compute unit
+// -> pace, from sweeps of 6 Llama shapes x 8 batch sizes (48 ... 512) x 8 slice counts (picks within 1.1 % of
+// the best swept plan on average, 7 % at worst).
 double estimate_us(const Problem &p, int t, int split)
 {
     const TileShape &ts = kTiles[t];
@@ -64,21 +74,33 @@ double estimate_us(const Problem &p, int t, int split)
     const int sps = ceil_div_i(stages, split);
     const int slices = ceil_div_i(stages, sps);
     const double wgs = (double)tiles * slices;
+    if (ts.resident > 0) {
+        const double n = wgs / kComputeUnits;  // workgroups per compute unit
+        // the busiest compute units set the time: ceil(n) resident there; past `resident` the rest queue up
+        double pace;
+        if (n >= ts.resident) {
+            pace = ts.pace[ts.resident - 1] * n / ts.resident;
+        } else {
+            const int r = (int)std::ceil(n - 1e-9);
+            pace = ts.pace[(r < 1 ? 1 : r) - 1];
+        }
+        double us = ts.fixed_us + sps * pace;
+        if (slices > 1)
+            us += 2.0 * wgs * ts.bm * ts.bn * sizeof(float) / (ts.scratch_tbps * 1e6);
+        return us;
+    }
     if (ts.pair_us > 0.0) {
         // whole waves of two workgroups per compute unit, then the rest: alone if it fits one per unit
         const int per_wave = 2 * kComputeUnits;
         const int waves = (int)wgs / per_wave;
         const int rest = (int)wgs - waves * per_wave;
-        double us = 3.5 + waves * (sps * ts.pair_us + 1.5) + (slices > 1 ? 5.0 : 0.0);
+        double us = 3.5 + waves * (sps * ts.pair_us + 1.5);
         if (rest > 0)
             us += sps * (rest > kComputeUnits ? ts.pair_us : ts.stage_us) + 1.5;
         return us;
     }
-    double rounds = ts.overlap > 1.0 ? wgs / (kComputeUnits * ts.overlap) : std::ceil(wgs / kComputeUnits);
-    if (rounds < 1.0)
-        rounds = 1.0;
-    // 1.5 us to fill and drain a workgroup's pipeline, 5 us for the combine of a split
-    return 3.5 + rounds * (sps * ts.stage_us + 1.5) + (slices > 1 ? 5.0 : 0.0);
+    // one workgroup per compute unit: whole rounds, 1.5 us each to fill and drain the pipeline
+    return 3.5 + std::ceil(wgs / kComputeUnits) * (sps * ts.stage_us + 1.5) + (slices > 1 ? 5.0 : 0.0);
 }
 
 int mode_of(const Problem &p)
@@ -188,8 +210,6 @@ hipError_t launch_prefill(const Problem &p, const PrefillPlan &plan, void *works
     case 8: return prefill::launch_tile<8>(a, mode, stream);
     case 9: return prefill::launch_tile<9>(a, mode, stream);
     case 10: return prefill::launch_tile<10>(a, mode, stream);
-    case 11: return prefill::launch_tile<11>(a, mode, stream);
-    case 12: return prefill::launch_tile<12>(a, mode, stream);
     default: return hipErrorInvalidValue;
     }
 }

@@ -64,7 +64,7 @@ struct Args {
     // [s * stages_per_slice, ...); the slices meet in scratch, in slice order, as in the other kernels.
     int split_k;            // 1 = no split
     int stages_per_slice;
-    float *partial;         // [split_k][tiles][accumulators per thread][256 threads] fp32
+    float *partial;         // [split_k][tiles][accumulators per thread][256 threads] fp32 (see combine_slices)
     unsigned *counters;     // [tiles], zero between launches
 };
 
@@ -178,6 +178,77 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[TM][TN], half_
             }
         }
     }
+}
+
+// K slices across workgroups (few output tiles, deep K).  Every slice leaves its results in scratch and the
+// last workgroup of the tile to arrive adds them in slice order (deterministic), then goes on to store the
+// tile.  The values travel in pairs - 64-bit accesses, pair p of thread t at [p][t]: coalesced - and the last
+// arriver loads several slices before it uses any, so the combine costs a few scratch round trips instead of
+// one per slice.  Device-scope accesses and an arrival counter, no device-wide fence (see the vector kernel).
+// Returns false in the workgroups that are not the last of their tile.  Partial layout:
+// [split_k][tiles][ACC / 2 pairs][256 threads] x 8 bytes.
+template <int ACC>
+__device__ __forceinline__ bool combine_slices(float (&v)[ACC], const Args &a, int slice, int tile_id, int tid)
+{
+    static_assert(ACC % 2 == 0, "values travel in pairs");
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    constexpr int PAIRS = ACC / 2;
+    constexpr int CH = PAIRS < 64 ? PAIRS : 64;  // pairs of one slice loaded together
+    constexpr int G = 64 / CH;                   // slices loaded together: up to 128 values in flight
+    static_assert(PAIRS % CH == 0, "whole batches");
+    __shared__ int s_last;
+    const size_t tiles = (size_t)a.tiles_m * a.tiles_n;
+    unsigned long long *scratch = reinterpret_cast<unsigned long long *>(a.partial);
+    unsigned long long *mine = scratch + ((size_t)slice * tiles + tile_id) * PAIRS * kThreads + tid;
+#pragma unroll
+    for (int p = 0; p < PAIRS; ++p) {
+        const f32x2_t pair = {v[2 * p], v[2 * p + 1]};
+        __hip_atomic_store(mine + (size_t)p * kThreads, __builtin_bit_cast(unsigned long long, pair), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);  // every partial store of this workgroup has been acknowledged
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned prev =
+            __hip_atomic_fetch_add(a.counters + tile_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = (prev == (unsigned)(a.split_k - 1));
+    }
+    __syncthreads();
+    if (!s_last)
+        return false;
+#pragma unroll
+    for (int e = 0; e < ACC; ++e)
+        v[e] = 0.f;
+#pragma unroll
+    for (int c0 = 0; c0 < PAIRS; c0 += CH) {
+        for (int sl0 = 0; sl0 < a.split_k; sl0 += G) {
+            unsigned long long part[G][CH];
+#pragma unroll
+            for (int u = 0; u < G; ++u) {
+                const int sl = min(sl0 + u, a.split_k - 1);  // unconditional loads; a repeated slice is not added
+                const unsigned long long *theirs =
+                    scratch + ((size_t)sl * tiles + tile_id) * PAIRS * kThreads + (size_t)c0 * kThreads + tid;
+#pragma unroll
+                for (int p = 0; p < CH; ++p)
+                    part[u][p] =
+                        __hip_atomic_load(theirs + (size_t)p * kThreads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int u = 0; u < G; ++u) {
+                const float keep = sl0 + u < a.split_k ? 1.f : 0.f;
+#pragma unroll
+                for (int p = 0; p < CH; ++p) {
+                    const f32x2_t pair = __builtin_bit_cast(f32x2_t, part[u][p]);
+                    v[2 * (c0 + p)] += keep * pair[0];
+                    v[2 * (c0 + p) + 1] += keep * pair[1];
+                }
+            }
+        }
+    }
+    if (tid == 0)
+        __hip_atomic_store(a.counters + tile_id, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+    return true;
 }
 
 // =====================================================================================================
@@ -542,31 +613,16 @@ __global__ __launch_bounds__(kThreads, (kWavesPerSimd<BM, BN>)) void prefill_pip
         asm volatile("" : "+v"(afr[0][i]), "+v"(afr[1][i]));
 
     if (a.split_k > 1) {
-        // ---- combine the K slices: every slice leaves its accumulators in scratch (element e of thread t at
-        //      [e][t]: coalesced), the last workgroup of the tile to arrive adds them in slice order.  Device
-        //      scope accesses and an arrival counter, no device-wide fence (see the vector kernel). ----
         constexpr int ACC = TM * TN * 16;
-        __shared__ int s_last;
-        const size_t tiles = (size_t)a.tiles_m * a.tiles_n;
-        float *mine = a.partial + ((size_t)slice * tiles + tile_id) * ACC * kThreads + tid;
+        float flat[ACC];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int t = 0; t < TN; ++t)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    __hip_atomic_store(mine + (size_t)((i * TN + t) * 16 + r) * kThreads, acc[i][t][r],
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_s_waitcnt(0);  // every partial store of this workgroup has been acknowledged
-        __syncthreads();
-        if (tid == 0) {
-            const unsigned prev =
-                __hip_atomic_fetch_add(a.counters + tile_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_last = (prev == (unsigned)(a.split_k - 1));
-        }
-        __syncthreads();
-        if (!s_last)
+                    flat[(i * TN + t) * 16 + r] = acc[i][t][r];
+        if (!combine_slices<ACC>(flat, a, slice, tile_id, tid))
             return;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -574,20 +630,7 @@ __global__ __launch_bounds__(kThreads, (kWavesPerSimd<BM, BN>)) void prefill_pip
             for (int t = 0; t < TN; ++t)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    acc[i][t][r] = 0.f;
-        for (int sl = 0; sl < a.split_k; ++sl) {
-            const float *theirs = a.partial + ((size_t)sl * tiles + tile_id) * ACC * kThreads + tid;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int t = 0; t < TN; ++t)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        acc[i][t][r] += __hip_atomic_load(theirs + (size_t)((i * TN + t) * 16 + r) * kThreads,
-                                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if (tid == 0)
-            __hip_atomic_store(a.counters + tile_id, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+                    acc[i][t][r] = flat[(i * TN + t) * 16 + r];
     }
     store_tile<TM, TN>(acc, a.out, m0 + wm * WAVE_M, col_raw, col_ok, kh, M, N);
 }

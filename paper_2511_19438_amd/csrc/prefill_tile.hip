@@ -1,9 +1,9 @@
 // Instantiates the MFMA kernels for ONE tile configuration (GPTQ_PREFILL_TILE, set on the compiler
 // command line) so that the configurations compile in parallel.
-#include "prefill_ksplit_kernel.h"
+#include "prefill_kernel.h"
 
 #ifndef GPTQ_PREFILL_TILE
-#error "compile with -DGPTQ_PREFILL_TILE=<1..12>"
+#error "compile with -DGPTQ_PREFILL_TILE=<1..10>"
 #endif
 
 namespace gptq {
@@ -35,10 +35,6 @@ constexpr int BM = 128, BN = 256, WM = 1, WN = 4, BK = 64, NBUF = 3;
 constexpr int BM = 256, BN = 256, WM = 2, WN = 2, BK = 64, NBUF = 3;
 #elif GPTQ_PREFILL_TILE == 10
 constexpr int BM = 256, BN = 256, WM = 2, WN = 2, BK = 32, NBUF = 6;
-#elif GPTQ_PREFILL_TILE == 11  // wavefronts split K inside the workgroup (prefill_ksplit_kernel)
-[[maybe_unused]] constexpr int BM = 64, BN = 128, WM = 1, WN = 1, BK = 64, NBUF = 4;
-#elif GPTQ_PREFILL_TILE == 12  // the same for up to 32 rows
-[[maybe_unused]] constexpr int BM = 32, BN = 128, WM = 1, WN = 1, BK = 64, NBUF = 6;
 #else
 #error "unknown tile id"
 #endif
@@ -71,18 +67,9 @@ hipError_t launch(Kernel kernel, Args a, size_t lds, bool may_split, hipStream_t
 template <>
 hipError_t launch_tile<GPTQ_PREFILL_TILE>(const Args &a, int mode, hipStream_t stream)
 {
-#if GPTQ_PREFILL_TILE >= 11
-    if (mode == kGroupPerStage) {
-        size_t lds = (size_t)NBUF * StageLayout<BM, BN, BK>::BYTES;  // the ring; the final reduction reuses it
-        if (lds < (size_t)kKsplitReduceBytes)
-            lds = kKsplitReduceBytes;
-        return launch(prefill_ksplit_kernel<BM, BN, NBUF>, a, lds, true, stream);
-    }
-#else
     if (mode == kGroupPerStage)
         return launch(prefill_pipelined_kernel<BM, BN, WM, WN, BK, NBUF>, a,
                       (size_t)NBUF * StageLayout<BM, BN, BK>::BYTES, true, stream);
-#endif
 #if GPTQ_PREFILL_TILE == 3
     const size_t lds = 2 * (size_t)BM * 64 * sizeof(half_t);
     if (mode == kGroupPerRow)
