@@ -69,8 +69,8 @@ enum gptq_status {
  * dequantise, stage activations on chip, contract, reduce the split-K partial sums on
  * chip and across workgroups, round once to fp16, store).  `out` is OVERWRITTEN and need
  * not be zeroed (unlike the accumulate-by-atomicAdd contract of Eq. 9-10).
- * By default M = 1 runs the bandwidth-bound split-K vector kernel, 2 <= M <= 32 (up to 48 on layers narrower
- * than 16384 columns) a small-batch MFMA kernel with the same split-K decomposition (when the format allows:
+ * By default M = 1 runs the bandwidth-bound split-K vector kernel, 2 <= M <= 32 a small-batch MFMA kernel
+ * with the same split-K decomposition (when the format allows:
  * no g_idx, group_size % 128 == 0; otherwise the vector kernel up to M = 16), larger M the big-tile fp16
  * MFMA kernel.
  * Accumulation is in fp32; the result differs from the exact sum by fp32 reassociation

@@ -84,18 +84,16 @@ int acquire_workspace(size_t bytes, void **out)
 // Default kernel by batch size, from measurement on Llama-shaped layers.  A single row is streamed fastest
 // by the vector kernel.  From two rows on the small-batch MFMA kernel wins: its time is nearly flat up to 16
 // rows and grows slowly to 32, where the vector kernel pays for every weight once per batch row.  Past 32
-// rows it runs as two launches, which the big-tile MFMA kernel (with K slices on few-tile shapes) beats from
-// about 48 rows on, earlier on very wide layers.
+// rows it would run as two launches, which the big-tile MFMA kernel with K slices beats on every Llama shape
+// measured (33-48 rows: 14-28 us against 18-37 us).
 constexpr int kVectorMaxM = 1;
 constexpr int kSmallBatchAutoMaxM = 32;
-constexpr int kSmallBatchTwoLaunchMaxM = 48;
-constexpr int kSmallBatchTwoLaunchMaxN = 16384;
 
 bool small_batch_by_default(const Problem &p)
 {
     if (!skinny_supported(p))
         return false;
-    return p.M <= kSmallBatchAutoMaxM || (p.M <= kSmallBatchTwoLaunchMaxM && p.N < kSmallBatchTwoLaunchMaxN);
+    return p.M <= kSmallBatchAutoMaxM;
 }
 
 // What a call resolves to: the kernel and its decomposition, after the automatic choices.

@@ -110,8 +110,7 @@ def test_default_dispatch_by_batch_size(lib):
     from paper_2511_19438_amd import binding
 
     q = binding.gptq_w4a16_plan_query
-    assert [q(M, 4096, 4096, 128).kernel for M in (1, 2, 3, 16, 32, 33, 48, 49, 2048)] == [1, 3, 3, 3, 3, 3, 3, 2, 2]
-    # past 32 rows only layers that are not very wide stay with the small-batch kernel (two launches)
+    assert [q(M, 4096, 4096, 128).kernel for M in (1, 2, 3, 16, 32, 33, 48, 49, 2048)] == [1, 3, 3, 3, 3, 2, 2, 2, 2]
     assert [q(M, 4096, 22016, 128).kernel for M in (32, 33, 48)] == [3, 2, 2]
     # act-order and group sizes the small-batch MFMA kernel does not take fall back
     assert q(8, 4096, 4096, 128, act_order=True).kernel == 1
