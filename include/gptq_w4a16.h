@@ -98,10 +98,9 @@ typedef struct gptq_w4a16_plan {
                         its 128x128 and 64x128 tiles); 0 auto */
     int tile;        /* vector kernel: columns per workgroup (16, 32, 64, 128 or 256);
                         small-batch MFMA kernel: columns per workgroup (64 or 256; anything else = auto);
-                        MFMA kernel: tile id 1..10 = rows x columns per workgroup (wavefront grid):
-                        1 256x256 (1x4), 2 256x128 (2x2), 3 128x128 (2x2), 4 128x256 (1x4, deep ring),
-                        5 64x128 (1x4), 6 32x256 (1x4), 7 256x256 (1x4, 32-k stages), 8 128x256 (1x4),
-                        9 256x256 (2x2), 10 256x256 (2x2, 32-k stages); 0 auto */
+                        MFMA kernel: tile id = rows x columns per workgroup (wavefront grid):
+                        1 256x256 (1x4), 3 128x128 (2x2), 5 64x128 (1x4), 8 128x256 (1x4, two workgroups
+                        per compute unit); 0 auto; any other id is GPTQ_INVALID_ARG */
     int flags;       /* 0, or (vector kernel only: M <= 4, no g_idx, group_size % 32 == 0, 64-column tiles) a set
                         of ablation switches that take one of the paper's techniques out each, for measuring its
                         gain in isolation (Table 3's columns at kernel level):

@@ -28,7 +28,7 @@ COMMON = ["--offload-arch=" + ARCH, "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc"
           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function"]
 
 DECODE_BATCHES = (1, 2, 4, 8, 16)
-PREFILL_TILES = (1, 2, 3, 4, 5, 6, 7, 8, 9, 10)
+PREFILL_TILES = (1, 3, 5, 8)
 
 
 def units():

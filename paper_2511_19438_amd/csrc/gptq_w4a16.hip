@@ -186,6 +186,8 @@ int check_plan(const gptq_w4a16_plan_t *plan)
     // the ablation switches belong to the vector kernel
     if (plan->flags < 0 || plan->flags > 15 || (plan->flags != 0 && plan->kernel != 1))
         return GPTQ_INVALID_ARG;
+    if (plan->kernel == 2 && plan->tile != 0 && !prefill_tile_exists(plan->tile))
+        return GPTQ_INVALID_ARG;
     for (int i = 0; i < 4; ++i)
         if (plan->reserved[i] != 0)
             return GPTQ_INVALID_ARG;

@@ -75,6 +75,7 @@ struct PrefillPlan {
     int split_k;  // K slices (pipelined kernel only), 0 = auto
 };
 bool prefill_supported(const Problem &p);
+bool prefill_tile_exists(int tile);  // the tile ids a plan may name
 void prefill_make_plan(const Problem &p, PrefillPlan &plan);
 // Scratch of a plan with split_k > 1 (counter area first, as for the other kernels); 0 without a split.
 size_t prefill_workspace_bytes(const Problem &p, const PrefillPlan &plan);

@@ -9,15 +9,9 @@ namespace prefill {
 template <int TILE>
 hipError_t launch_tile(const Args &a, int mode, hipStream_t stream);
 template <> hipError_t launch_tile<1>(const Args &, int, hipStream_t);
-template <> hipError_t launch_tile<2>(const Args &, int, hipStream_t);
 template <> hipError_t launch_tile<3>(const Args &, int, hipStream_t);
-template <> hipError_t launch_tile<4>(const Args &, int, hipStream_t);
 template <> hipError_t launch_tile<5>(const Args &, int, hipStream_t);
-template <> hipError_t launch_tile<6>(const Args &, int, hipStream_t);
-template <> hipError_t launch_tile<7>(const Args &, int, hipStream_t);
 template <> hipError_t launch_tile<8>(const Args &, int, hipStream_t);
-template <> hipError_t launch_tile<9>(const Args &, int, hipStream_t);
-template <> hipError_t launch_tile<10>(const Args &, int, hipStream_t);
 }  // namespace prefill
 
 namespace {
@@ -37,19 +31,20 @@ struct TileShape {
     double fixed_us;
     double scratch_tbps;
 };
-// ids 1..10, see the plan documentation in the public header
+// by tile id (1, 3, 5, 8: see the plan documentation in the public header; the other ids up to 10 belonged to
+// layouts that measurement retired - 2x2 wavefront grids, 32-k stages, a 32-row tile - and are refused)
 constexpr TileShape kTiles[11] = {
     {0, 0, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
     {256, 256, 64, 1.25, false, 0.0, 0, {0, 0, 0}, 0, 0},
-    {256, 128, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
+    {0, 0, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
     {128, 128, 64, 0.75, true, 0.0, 2, {0.75, 1.4, 0}, 7.0, 6.0},
-    {128, 256, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
+    {0, 0, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
     {64, 128, 64, 0.46, true, 0.0, 3, {0.46, 0.72, 1.0}, 6.0, 6.0},
-    {32, 256, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
-    {256, 256, 32, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
+    {0, 0, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
+    {0, 0, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
     {128, 256, 64, 0.99, false, 1.31, 0, {0, 0, 0}, 0, 0},
-    {256, 256, 64, 1.40, false, 0.0, 0, {0, 0, 0}, 0, 0},
-    {256, 256, 32, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0}};
+    {0, 0, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
+    {0, 0, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0}};
 constexpr int kNumTiles = 10;
 constexpr int kComputeUnits = 256;
 constexpr size_t kCounterBytes = 256 * 1024;  // same fixed counter area as the other kernels
@@ -119,6 +114,11 @@ bool prefill_supported(const Problem &p)
     return p.M >= 1 && p.K % 8 == 0 && p.N % 8 == 0;
 }
 
+bool prefill_tile_exists(int tile)
+{
+    return tile >= 1 && tile <= kNumTiles && kTiles[tile].bm > 0;
+}
+
 void prefill_make_plan(const Problem &p, PrefillPlan &plan)
 {
     const int mode = mode_of(p);
@@ -127,13 +127,8 @@ void prefill_make_plan(const Problem &p, PrefillPlan &plan)
         plan.split_k = 1;
         return;
     }
-    const bool tile_given = plan.tile >= 1 && plan.tile <= kNumTiles;
+    const bool tile_given = prefill_tile_exists(plan.tile);
     const bool split_given = plan.split_k >= 1;
-    if (tile_given && kTiles[plan.tile].stage_us <= 0.0) {  // a tile that is only ever requested: honour it as it is
-        if (!split_given)
-            plan.split_k = 1;
-        return;
-    }
     // Few output tiles and a deep K leave most of the chip idle and every workgroup walking all of K: K slices
     // (combined through scratch in slice order) shorten the walk.  Cheapest (tile, split) by the estimate.
     double best = 0.0;
@@ -170,7 +165,7 @@ void prefill_make_plan(const Problem &p, PrefillPlan &plan)
 
 size_t prefill_workspace_bytes(const Problem &p, const PrefillPlan &plan)
 {
-    if (plan.split_k <= 1 || plan.tile < 1 || plan.tile > kNumTiles)
+    if (plan.split_k <= 1 || !prefill_tile_exists(plan.tile))
         return 0;
     const TileShape &ts = kTiles[plan.tile];
     const size_t tiles = (size_t)ceil_div_i(p.M, ts.bm) * ceil_div_i(p.N, ts.bn);
@@ -201,15 +196,9 @@ hipError_t launch_prefill(const Problem &p, const PrefillPlan &plan, void *works
     const int mode = mode_of(p);
     switch (plan.tile) {
     case 1: return prefill::launch_tile<1>(a, mode, stream);
-    case 2: return prefill::launch_tile<2>(a, mode, stream);
     case 3: return prefill::launch_tile<3>(a, mode, stream);
-    case 4: return prefill::launch_tile<4>(a, mode, stream);
     case 5: return prefill::launch_tile<5>(a, mode, stream);
-    case 6: return prefill::launch_tile<6>(a, mode, stream);
-    case 7: return prefill::launch_tile<7>(a, mode, stream);
     case 8: return prefill::launch_tile<8>(a, mode, stream);
-    case 9: return prefill::launch_tile<9>(a, mode, stream);
-    case 10: return prefill::launch_tile<10>(a, mode, stream);
     default: return hipErrorInvalidValue;
     }
 }

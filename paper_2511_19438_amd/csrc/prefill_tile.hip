@@ -3,7 +3,7 @@
 #include "prefill_kernel.h"
 
 #ifndef GPTQ_PREFILL_TILE
-#error "compile with -DGPTQ_PREFILL_TILE=<1..10>"
+#error "compile with -DGPTQ_PREFILL_TILE=<1|3|5|8>"
 #endif
 
 namespace gptq {
@@ -17,24 +17,12 @@ namespace {
 // rows x columns per workgroup, wavefront grid, k per stage, stage buffers in the LDS ring
 #if GPTQ_PREFILL_TILE == 1
 constexpr int BM = 256, BN = 256, WM = 1, WN = 4, BK = 64, NBUF = 3;
-#elif GPTQ_PREFILL_TILE == 2
-constexpr int BM = 256, BN = 128, WM = 2, WN = 2, BK = 64, NBUF = 4;
 #elif GPTQ_PREFILL_TILE == 3
 constexpr int BM = 128, BN = 128, WM = 2, WN = 2, BK = 64, NBUF = 3;
-#elif GPTQ_PREFILL_TILE == 4
-constexpr int BM = 128, BN = 256, WM = 1, WN = 4, BK = 64, NBUF = 6;
 #elif GPTQ_PREFILL_TILE == 5
 constexpr int BM = 64, BN = 128, WM = 1, WN = 4, BK = 64, NBUF = 4;
-#elif GPTQ_PREFILL_TILE == 6
-constexpr int BM = 32, BN = 256, WM = 1, WN = 4, BK = 64, NBUF = 4;
-#elif GPTQ_PREFILL_TILE == 7
-constexpr int BM = 256, BN = 256, WM = 1, WN = 4, BK = 32, NBUF = 7;
 #elif GPTQ_PREFILL_TILE == 8
 constexpr int BM = 128, BN = 256, WM = 1, WN = 4, BK = 64, NBUF = 3;
-#elif GPTQ_PREFILL_TILE == 9
-constexpr int BM = 256, BN = 256, WM = 2, WN = 2, BK = 64, NBUF = 3;
-#elif GPTQ_PREFILL_TILE == 10
-constexpr int BM = 256, BN = 256, WM = 2, WN = 2, BK = 32, NBUF = 6;
 #else
 #error "unknown tile id"
 #endif

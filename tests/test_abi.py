@@ -92,6 +92,12 @@ def test_plan_validation(lib):
     bad = binding.Plan()
     bad.reserved[2] = 7
     assert lib.gptq_w4a16_gemm_plan(p, p, p, p, None, p, 1, 128, 8, 128, None, ctypes.byref(bad)) == -1
+    # the big-tile kernel has four tile shapes; other ids are refused
+    for tile in (2, 4, 6, 7, 9, 10, 11):
+        bad = binding.Plan(kernel=2, tile=tile)
+        assert lib.gptq_w4a16_gemm_plan(p, p, p, p, None, p, 64, 128, 32, 128, None, ctypes.byref(bad)) == -1
+    for tile in (1, 3, 5, 8):
+        assert binding.gptq_w4a16_plan_query(512, 4096, 4096, 128, plan=binding.Plan(kernel=2, tile=tile)).tile == tile
 
 
 def test_workspace_bytes_is_host_only_and_monotone_in_batch(lib):

@@ -210,7 +210,7 @@ def test_prefill_gemm_matches_oracle(B, M, K, N, group, act):
     assert_within_band(out, ref, f"prefill M={M} K={K} N={N} g={group} act={act}")
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("tile", [1, 3, 5, 8])
 @pytest.mark.parametrize("M,N", [(300, 328), (32, 520), (300, 544), (1, 256)])
 def test_prefill_tiles_match_oracle(B, tile, M, N):
     K, group = 1024, 128
@@ -220,7 +220,7 @@ def test_prefill_tiles_match_oracle(B, tile, M, N):
     assert_within_band(out, ref, f"prefill tile={tile} M={M} N={N}")
 
 
-@pytest.mark.parametrize("tile", [1, 3, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("tile", [1, 3, 5, 8])
 @pytest.mark.parametrize("split_k", [2, 3, 7, 32])
 @pytest.mark.parametrize("M,N", [(300, 544), (40, 288)])
 def test_prefill_k_split_matches_oracle(B, tile, split_k, M, N):
