@@ -225,14 +225,14 @@ def graph_us(torch, launches, reps=6):
 
 
 def sweep_tables(torch, B, workloads, layers):
-    """Side tables (not the headline): the decode batch sweep on the Llama-7B shapes, the act-order layer with
+    """Side tables (not the headline): the decode and mid batch sweep on the Llama-7B shapes, the act-order layer with
     its g_idx kernels and repacked, and single-row GEMVs on the Llama-70B shapes.  Every launch streams its
     weights from HBM (the launches of a graph rotate over distinct weight copies larger than the caches)."""
     shapes = workloads.LLAMA_7B
     out = {"unit": "us per launch (GB/s of algorithmic bytes)", "llama7b": [], "act_order": [], "llama70b": []}
     for si, sh in enumerate(shapes):
         row = {"shape": f"{sh.name} K={sh.K} N={sh.N}"}
-        for M in workloads.DECODE_BATCHES:
+        for M in workloads.DECODE_BATCHES + workloads.MID_BATCHES:
             x = torch.randn((M, sh.K), device="cuda").half()
             o = torch.empty((M, sh.N), dtype=torch.float16, device="cuda")
             fns = [(lambda t=mats[si]: B.gptq_w4a16_gemm(x, t["qweight"], t["qzeros"], t["scales"], None, o, GROUP))

@@ -54,6 +54,7 @@ LLAMA_70B: List[Shape] = [
 ACT_ORDER_SHAPE = Shape("act_order", 4096, 11008)
 
 DECODE_BATCHES = (1, 2, 4, 8, 16)
+MID_BATCHES = (32, 64, 128)
 PREFILL_BATCHES = (512, 2048)
 
 
