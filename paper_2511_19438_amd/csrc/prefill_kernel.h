@@ -359,35 +359,44 @@ __global__ __launch_bounds__(kThreads, (kWavesPerSimd<BM, BN>)) void prefill_pip
     const uint32_t sz_stride = sz_is_scale ? (uint32_t)N * 2u : (uint32_t)(N >> 3) * 4u;  // bytes per group row
     const int stages_per_group = a.group_size / BK;
 
-    // The stage whose loads are issued next, kept incrementally (no division in the loop).
-    int ld_stage = first, ld_group = first / stages_per_group, ld_in_group = first % stages_per_group;
+    // The stage whose loads are issued next, as running source pointers (uniform for the activations and the
+    // packed words, per lane for the scales / zero points) that advance by constants: no multiplication and no
+    // division in the loop, and selects instead of branches - a branch would end the basic block, and the
+    // dequantisation of a stage's last k step (pure arithmetic, first used in the next stage) would sink
+    // across it, out of the MFMAs' shadow.
+    int ld_stage = first, ld_in_group = first % stages_per_group;
+    const char *a_cur = a_base + (size_t)first * BK * 2;
+    const size_t b_step = (size_t)(BK / 8) * N * 4;  // bytes between the packed rows of consecutive stages
+    const char *b_cur = b_base + (size_t)first * b_step;
+    const char *sz_cur = sz_src + (size_t)(first / stages_per_group) * sz_stride;
     auto stage_base = [&](int ring) { return smem + (size_t)ring * L::BYTES; };
     // piece `p` (0 .. LOADS_PER_STAGE-1) of the loads of stage `ld_stage` into ring slot `ring`
     auto issue_piece = [&](int p, int ring) {
         unsigned char *base = stage_base(ring);
-        const size_t k0 = (size_t)ld_stage * BK;
         if (p < A_CHUNKS) {  // the wave's 64 lanes fill 64 consecutive 16-byte slots
-            __builtin_amdgcn_global_load_lds((global_ptr_t *)(a_base + k0 * 2 + a_off[p]),
+            __builtin_amdgcn_global_load_lds((global_ptr_t *)(a_cur + a_off[p]),
                                              (lds_ptr_t *)(base + (size_t)(p * kThreads + wave * 64) * 16), 16, 0, 0);
         } else if (p < A_CHUNKS + B_CHUNKS) {
             const int j = p - A_CHUNKS;
-            __builtin_amdgcn_global_load_lds((global_ptr_t *)(b_base + (k0 / 8) * N * 4 + b_off[j]),
+            __builtin_amdgcn_global_load_lds((global_ptr_t *)(b_cur + b_off[j]),
                                              (lds_ptr_t *)(base + L::A_BYTES + (size_t)(j * kThreads + wave * 64) * 16),
                                              16, 0, 0);
         } else {
             // all four waves write the same bytes: keeps the per-wave count of outstanding loads identical
-            __builtin_amdgcn_global_load_lds((global_ptr_t *)(sz_src + (size_t)ld_group * sz_stride),
-                                             (lds_ptr_t *)(base + L::A_BYTES + L::B_BYTES), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((global_ptr_t *)sz_cur, (lds_ptr_t *)(base + L::A_BYTES + L::B_BYTES),
+                                             16, 0, 0);
         }
     };
     auto advance_load_stage = [&]() {
-        if (ld_stage < last) {  // past the end the last stage is refetched: uniform counts, no branch in the loads
-            ++ld_stage;
-            if (++ld_in_group == stages_per_group) {
-                ld_in_group = 0;
-                ++ld_group;
-            }
-        }
+        // past the end the last stage is refetched: uniform counts, no branch in the loads
+        const int more = ld_stage < last ? 1 : 0;
+        ld_stage += more;
+        a_cur += more ? BK * 2 : 0;
+        b_cur += more ? b_step : (size_t)0;
+        ld_in_group += more;
+        const bool wrap = ld_in_group == stages_per_group;
+        ld_in_group = wrap ? 0 : ld_in_group;
+        sz_cur += wrap ? sz_stride : 0u;
     };
     // Publish the oldest batch in flight: every wave waits for its own part of it, the barrier does the rest.
     auto publish = [&]() {
