@@ -31,12 +31,12 @@ struct Derived {
 Derived derive(const Problem &p, int cols_per_wg, int chunk_rows)
 {
     Derived d;
+    const int mb = batch_template(p.M < 16 ? p.M : 16);
     d.lpr = cols_per_wg / 4;
-    d.rw = decode::kWaves * (64 / d.lpr);
+    d.rw = decode::waves_for(mb, p.g_idx != nullptr) * (64 / d.lpr);
     d.rows = p.K / 8;
     d.total_chunks = ceil_div(d.rows, chunk_rows);
     d.tiles_n = ceil_div(p.N, cols_per_wg);
-    const int mb = batch_template(p.M < 16 ? p.M : 16);
     int ls_max = kMaxSliceLdsBytes / (2 * mb);  // activations per batch row per slice
     if (ls_max > 16384)
         ls_max = 16384;
@@ -228,7 +228,7 @@ hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspa
         size_t lds = ((size_t)mb * ls * sizeof(half_t) + 15) & ~(size_t)15;
         if (!act && mb < 8)  // per-chunk sums of the activations (must mirror the kernel's carve-up)
             lds += ((size_t)mb * plan.chunks_per_slice * 2 * sizeof(float) + 15) & ~(size_t)15;
-        lds += (size_t)decode::kWaves * mc * plan.cols_per_wg * sizeof(float);
+        lds += (size_t)decode::waves_for(mb, act) * mc * plan.cols_per_wg * sizeof(float);
         if (act)
             lds += (size_t)ls * sizeof(int) + (size_t)a.groups * plan.cols_per_wg * sizeof(uint32_t);
         if (lds > kMaxLdsBytes)

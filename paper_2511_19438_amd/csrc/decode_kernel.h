@@ -26,8 +26,14 @@
 namespace gptq {
 namespace decode {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = 4;
+// Wavefronts per workgroup.  The single-row kernel of the plain format runs eight (two per SIMD): a wavefront
+// issues one instruction every few cycles whatever its kind, and with a second one on the SIMD the loads, LDS
+// reads, matrix-unit and scalar instructions of one overlap the vector arithmetic of the other (measured 3-8 %
+// on the Llama GEMVs; sixteen were twice as slow).  The other variants keep four.
+constexpr int waves_for(int mb, bool act)
+{
+    return (mb == 1 && !act) ? 8 : 4;
+}
 
 struct Args {
     const half_t *x;
@@ -146,10 +152,12 @@ constexpr int kMatrixDot = 8;
 constexpr int kGatherX = 16;
 
 template <int MB, int LPR, int R, bool ACT, int ABL = 0>
-__global__ __launch_bounds__(kThreads) void decode_kernel(const Args a)
+__global__ __launch_bounds__(64 * waves_for(MB, ACT)) void decode_kernel(const Args a)
 {
     static_assert(ABL == 0 || (!ACT && MB < 8), "the ablation variants exist for the plain format at small batch");
     static_assert(!(ABL & kMatrixDot) || MB <= 4, "the 4x4x4 matrix product carries four batch rows");
+    constexpr int kWaves = waves_for(MB, ACT);
+    constexpr int kThreads = 64 * kWaves;
     constexpr int RL = 64 / LPR;          // row lanes per wavefront
     constexpr int RW = kWaves * RL;       // row lanes per workgroup
     constexpr int CT = LPR * 4;           // columns per workgroup

@@ -21,7 +21,7 @@ hipError_t launch_one(const Args &a, size_t lds_bytes, hipStream_t stream)
         if (err != hipSuccess)
             return err;
     }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.tiles_n * a.split_k)), dim3(kThreads), lds_bytes, stream, a);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.tiles_n * a.split_k)), dim3(64 * waves_for(MB, ACT)), lds_bytes, stream, a);
     return hipGetLastError();
 }
 
