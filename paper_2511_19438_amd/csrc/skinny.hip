@@ -28,17 +28,23 @@ int rows_of_launch(int M)
     return M < kRowsPerLaunch ? M : kRowsPerLaunch;
 }
 
-template <int TM, int WN>
+// Wavefronts per workgroup: eight where the 64-column workgroups have a compute unit each, else four.
+int waves_of(int tiles_n, int split_k, int wn)
+{
+    return (wn == 1 && (long long)tiles_n * split_k <= 256) ? 8 : 4;
+}
+
+template <int TM, int WN, int WAVES>
 hipError_t launch_tm(const skinny::Args &a, size_t lds, hipStream_t stream)
 {
-    auto kernel = skinny::skinny_kernel<TM, WN>;
+    auto kernel = skinny::skinny_kernel<TM, WN, WAVES>;
     if (lds > 48 * 1024) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (err != hipSuccess)
             return err;
     }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.tiles_n * a.split_k)), dim3(skinny::kThreads), lds, stream, a);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.tiles_n * a.split_k)), dim3(64 * WAVES), lds, stream, a);
     return hipGetLastError();
 }
 
@@ -67,7 +73,6 @@ void skinny_make_plan(const Problem &p, SkinnyPlan &plan)
     if (max_units < 1)
         max_units = 1;
     const int tiles_n = ceil_div(p.N, plan.cols_per_wg);
-    const int quantum = plan.cols_per_wg == 64 ? 4 : 1;  // narrow tiles: one unit per wavefront and turn
     int ups;
     if (plan.split_k > 0) {
         ups = ceil_div(total_units, plan.split_k < total_units ? plan.split_k : total_units);
@@ -85,6 +90,8 @@ void skinny_make_plan(const Problem &p, SkinnyPlan &plan)
             split = max_split;
         if (split < 1)
             split = 1;
+        // narrow tiles: one unit per wavefront and turn
+        const int quantum = plan.cols_per_wg == 64 ? waves_of(tiles_n, split, 1) : 1;
         ups = ceil_div(ceil_div(total_units, split), quantum) * quantum;
         if (ups > total_units)
             ups = total_units;
@@ -138,13 +145,16 @@ hipError_t launch_skinny(const Problem &p, const SkinnyPlan &plan, void *workspa
         const size_t xs = direct ? 0
                                  : (size_t)rows * plan.units_per_slice * skinny::kUnitK * sizeof(half_t)  // activations
                                        + (size_t)rows * plan.units_per_slice * 8;                        // and their sums
-        const size_t red = (size_t)skinny::kWaves * rows * skinny::kCols * sizeof(float);  // [4/wn][rows][64*wn]
+        const int waves = waves_of(a.tiles_n, a.split_k, wn);
+        const size_t red = (size_t)waves * rows * skinny::kCols * sizeof(float);  // [waves/wn][rows][64*wn]
         const size_t lds = xs > red ? xs : red;
         hipError_t err;
         if (wn == 4)
-            err = tm == 1 ? launch_tm<1, 4>(a, lds, stream) : launch_tm<2, 4>(a, lds, stream);
+            err = tm == 1 ? launch_tm<1, 4, 4>(a, lds, stream) : launch_tm<2, 4, 4>(a, lds, stream);
+        else if (waves == 8)
+            err = tm == 1 ? launch_tm<1, 1, 8>(a, lds, stream) : launch_tm<2, 1, 8>(a, lds, stream);
         else
-            err = tm == 1 ? launch_tm<1, 1>(a, lds, stream) : launch_tm<2, 1>(a, lds, stream);
+            err = tm == 1 ? launch_tm<1, 1, 4>(a, lds, stream) : launch_tm<2, 1, 4>(a, lds, stream);
         if (err != hipSuccess)
             return err;
     }

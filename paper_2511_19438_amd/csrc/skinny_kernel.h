@@ -26,8 +26,6 @@
 namespace gptq {
 namespace skinny {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = 4;
 constexpr int kCols = 64;      // columns per workgroup
 constexpr int kUnitK = 128;    // k per pipeline unit (4 MFMA steps of 32)
 
@@ -93,9 +91,17 @@ struct UnitRegs {
 // workgroup owns 64 columns and its four wavefronts split the K slice (narrow layers: many small
 // workgroups); with WN = 4 it owns 256 columns, every wavefront walks the whole slice for its own 64
 // columns and the staged activations serve four times as many weights (wide layers).
-template <int TM, int WN>
-__global__ __launch_bounds__(kThreads) void skinny_kernel(const Args a)
+//
+// WAVES wavefronts per workgroup: four, or - 64-column workgroups that have a compute unit to themselves -
+// eight, two per SIMD, so that the loads, LDS and scalar instructions of one overlap the arithmetic of the
+// other (3-11 % on the narrow and deep Llama layers; with more workgroups than compute units the co-resident
+// workgroups already do that, and eight wavefronts each measured 3-12 % slower).
+template <int TM, int WN, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
 {
+    static_assert(WAVES == 4 || (WAVES == 8 && WN == 1), "eight wavefronts only where they split the slice");
+    constexpr int kWaves = WAVES;
+    constexpr int kThreads = 64 * WAVES;
     constexpr int ROWS = 16 * TM;
     constexpr int COLS = kCols * WN;   // columns per workgroup
     constexpr int KW = kWaves / WN;    // wavefronts that share a column block and split the slice
