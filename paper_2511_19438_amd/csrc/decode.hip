@@ -28,12 +28,19 @@ struct Derived {
     int lpr, rw, rows, total_chunks, tiles_n, max_chunks_per_slice;
 };
 
+// Wavefronts per workgroup: eight for the single-row kernel of the plain format (chunks of four packed rows)
+// when every workgroup has a compute unit to itself, else four (see decode::kEightWaves).
+int decode_waves(int mb, bool act, int chunk_rows, long long workgroups)
+{
+    return (mb == 1 && !act && chunk_rows == 4 && workgroups <= 256) ? 8 : 4;
+}
+
 Derived derive(const Problem &p, int cols_per_wg, int chunk_rows)
 {
     Derived d;
     const int mb = batch_template(p.M < 16 ? p.M : 16);
     d.lpr = cols_per_wg / 4;
-    d.rw = decode::waves_for(mb, p.g_idx != nullptr) * (64 / d.lpr);
+    d.rw = 4 * (64 / d.lpr);  // with four wavefronts; eight where decode_waves() says so
     d.rows = p.K / 8;
     d.total_chunks = ceil_div(d.rows, chunk_rows);
     d.tiles_n = ceil_div(p.N, cols_per_wg);
@@ -103,7 +110,6 @@ void decode_make_plan(const Problem &p, DecodePlan &plan)
             continue;
         const Derived d = derive(p, tile, plan.chunk_rows);
         const int step_chunks = d.rw * (act ? 1 : 2);  // chunks one workgroup consumes per pipeline step
-        const int max_steps = ceil_div(d.total_chunks, step_chunks);
         if (plan.split_k > 0) {
             const int split = plan.split_k < d.total_chunks ? plan.split_k : d.total_chunks;
             int cps = ceil_div(d.total_chunks, split);
@@ -115,21 +121,31 @@ void decode_make_plan(const Problem &p, DecodePlan &plan)
             }
             continue;
         }
-        int last_slices = 0;
-        for (int steps = 1; steps <= max_steps; ++steps) {
-            int cps = steps * step_chunks;
-            if (cps > d.max_chunks_per_slice) {
-                if (steps > 1)
-                    break;
-                cps = d.max_chunks_per_slice;
-            }
-            const int slices = ceil_div(d.total_chunks, cps);
-            if (slices == last_slices)
-                continue;  // same slice count as with the shorter slices before: only less balanced
-            last_slices = slices;
-            const double t = estimate_us(p, d, tile, plan.chunk_rows, cps, act);
-            if (!best_tile || t < best_t - 1e-9) {
-                best_tile = tile, best_cps = cps, best_t = t;
+        // slice lengths of whole steps, for the step of either wavefront count; a candidate stands if its
+        // workgroup count calls for the wavefront count it was made for
+        const int mb = batch_template(p.M < 16 ? p.M : 16);
+        for (int waves = 8; waves >= 4; waves -= 4) {
+            if (waves == 8 && decode_waves(mb, act, plan.chunk_rows, 1) != 8)
+                continue;
+            const int step = step_chunks * waves / 4;
+            int last_slices = 0;
+            for (int steps = 1; steps <= ceil_div(d.total_chunks, step); ++steps) {
+                int cps = steps * step;
+                if (cps > d.max_chunks_per_slice) {
+                    if (steps > 1)
+                        break;
+                    cps = d.max_chunks_per_slice;
+                }
+                const int slices = ceil_div(d.total_chunks, cps);
+                if (slices == last_slices)
+                    continue;  // same slice count as with the shorter slices before: only less balanced
+                last_slices = slices;
+                if (decode_waves(mb, act, plan.chunk_rows, (long long)d.tiles_n * slices) != waves)
+                    continue;
+                const double t = estimate_us(p, d, tile, plan.chunk_rows, cps, act);
+                if (!best_tile || t < best_t - 1e-9) {
+                    best_tile = tile, best_cps = cps, best_t = t;
+                }
             }
         }
     }
@@ -228,7 +244,8 @@ hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspa
         size_t lds = ((size_t)mb * ls * sizeof(half_t) + 15) & ~(size_t)15;
         if (!act && mb < 8)  // per-chunk sums of the activations (must mirror the kernel's carve-up)
             lds += ((size_t)mb * plan.chunks_per_slice * 2 * sizeof(float) + 15) & ~(size_t)15;
-        lds += (size_t)decode::waves_for(mb, act) * mc * plan.cols_per_wg * sizeof(float);
+        const int waves = decode_waves(mb, act, plan.chunk_rows, (long long)d.tiles_n * plan.split_k);
+        lds += (size_t)waves * mc * plan.cols_per_wg * sizeof(float);
         if (act)
             lds += (size_t)ls * sizeof(int) + (size_t)a.groups * plan.cols_per_wg * sizeof(uint32_t);
         if (lds > kMaxLdsBytes)
@@ -241,7 +258,7 @@ hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspa
             if (hipGetLastError() != hipSuccess)
                 return hipErrorLaunchFailure;
         }
-        const int flags = plan.flags | (p.x_perm ? decode::kGatherX : 0);
+        const int flags = plan.flags | (p.x_perm ? decode::kGatherX : 0) | (waves == 8 ? decode::kEightWaves : 0);
         hipError_t err;
         switch (mb) {
         case 1: err = decode::launch_mb<1>(a, d.lpr, plan.chunk_rows, act, flags, lds, stream); break;

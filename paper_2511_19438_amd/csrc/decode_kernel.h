@@ -26,15 +26,6 @@
 namespace gptq {
 namespace decode {
 
-// Wavefronts per workgroup.  The single-row kernel of the plain format runs eight (two per SIMD): a wavefront
-// issues one instruction every few cycles whatever its kind, and with a second one on the SIMD the loads, LDS
-// reads, matrix-unit and scalar instructions of one overlap the vector arithmetic of the other (measured 3-8 %
-// on the Llama GEMVs; sixteen were twice as slow).  The other variants keep four.
-constexpr int waves_for(int mb, bool act)
-{
-    return (mb == 1 && !act) ? 8 : 4;
-}
-
 struct Args {
     const half_t *x;
     const uint32_t *qweight;
@@ -150,13 +141,20 @@ constexpr int kMatrixDot = 8;
 // Another variant: the activations are gathered through Args::x_perm while they are staged (the weight's rows
 // were sorted by group once, so that it reads like the plain format; the activations follow them per call).
 constexpr int kGatherX = 16;
+// Eight wavefronts per workgroup (two per SIMD) instead of four, for the single-row kernel of the plain format
+// where every workgroup has a compute unit to itself: a wavefront issues one instruction every few cycles
+// whatever its kind, and with a second one on the SIMD the loads, LDS reads, matrix-unit and scalar
+// instructions of one overlap the vector arithmetic of the other (measured 3-8 % on the Llama GEMVs; sixteen
+// were twice as slow, and with more workgroups than compute units eight are 2-5 % slower than four).
+constexpr int kEightWaves = 32;
 
 template <int MB, int LPR, int R, bool ACT, int ABL = 0>
-__global__ __launch_bounds__(64 * waves_for(MB, ACT)) void decode_kernel(const Args a)
+__global__ __launch_bounds__((ABL & kEightWaves) ? 512 : 256) void decode_kernel(const Args a)
 {
     static_assert(ABL == 0 || (!ACT && MB < 8), "the ablation variants exist for the plain format at small batch");
     static_assert(!(ABL & kMatrixDot) || MB <= 4, "the 4x4x4 matrix product carries four batch rows");
-    constexpr int kWaves = waves_for(MB, ACT);
+    static_assert(!(ABL & kEightWaves) || (MB == 1 && !ACT), "eight wavefronts: single row, plain format");
+    constexpr int kWaves = (ABL & kEightWaves) ? 8 : 4;
     constexpr int kThreads = 64 * kWaves;
     constexpr int RL = 64 / LPR;          // row lanes per wavefront
     constexpr int RW = kWaves * RL;       // row lanes per workgroup
