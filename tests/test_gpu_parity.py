@@ -503,3 +503,37 @@ def test_other_group_sizes_including_one_group_per_column(B, M, group):
     case = workloads.make_case(M, K, N, group, seed=33 + group)
     ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
     assert_within_band(run_gemm(B, case, group), ref, f"group={group} M={M}")
+
+
+# ------------------------------------------------------------------ HIP graph replay
+
+@pytest.mark.parametrize("M,K,N,plan_args", [
+    (1, 2816, 520, dict(kernel=1, split_k=4, tile=32)),   # vector kernel, K slices through scratch
+    (8, 2048, 328, dict(kernel=3, split_k=3)),            # small-batch MFMA kernel, K slices
+    (96, 1408, 288, dict(kernel=2, tile=5, split_k=3)),   # big-tile kernel, K slices
+    (1, 1024, 264, dict()),                                # default dispatch
+])
+def test_graph_replays_match_eager(B, M, K, N, plan_args):
+    """A captured launch replayed several times, with eager launches of other problems (which use the same
+    scratch and arrival counters) and synchronisations in between, gives the eager result bit for bit every time."""
+    group = 128
+    case = workloads.make_case(M, K, N, group, seed=M + K + N)
+    other = workloads.make_case(3, 1024, 520, group, seed=99)
+    plan = B.Plan(**plan_args) if plan_args else None
+    eager = run_gemm(B, case, group, plan)
+    x, qw, qz, sc = (dev(case[k]) for k in ("x", "qweight", "qzeros", "scales"))
+    out = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        B.gptq_w4a16_gemm(x, qw, qz, sc, None, out, group, plan)  # sizes the scratch before capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            B.gptq_w4a16_gemm(x, qw, qz, sc, None, out, group, plan)
+        for rep in range(4):
+            out.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            assert np.array_equal(got.view(np.uint16), eager.view(np.uint16)), f"replay {rep} differs from eager"
+            run_gemm(B, other, group, B.Plan(kernel=1, split_k=2, tile=64))  # eager work between the replays
