@@ -341,7 +341,13 @@ def context_lines(torch, reps=10):
     e1.record()
     torch.cuda.synchronize()
     dense = 2.0 * M * K * N * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
-    return {"device_copy_GBps_read_plus_write": round(copy_gbs, 1),
+    props = torch.cuda.get_device_properties(0)
+    device = {"name": props.name, "arch": getattr(props, "gcnArchName", ""), "compute_units": props.multi_processor_count,
+              "memory_GiB": round(props.total_memory / 2**30, 1)}
+    clock_khz = getattr(props, "clock_rate", 0)
+    if clock_khz:
+        device["max_clock_MHz"] = round(clock_khz / 1e3)
+    return {"device": device, "device_copy_GBps_read_plus_write": round(copy_gbs, 1),
             "torch_matmul_fp16_dense_TFLOPs_M2048_K4096_N22016": round(dense, 1)}
 
 
