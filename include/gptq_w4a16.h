@@ -69,10 +69,10 @@ enum gptq_status {
  * dequantise, stage activations on chip, contract, reduce the split-K partial sums on
  * chip and across workgroups, round once to fp16, store).  `out` is OVERWRITTEN and need
  * not be zeroed (unlike the accumulate-by-atomicAdd contract of Eq. 9-10).
- * By default M = 1 runs the bandwidth-bound split-K vector kernel, 2 <= M <= 32 a small-batch MFMA kernel
- * with the same split-K decomposition (when the format allows:
- * no g_idx, group_size % 128 == 0; otherwise the vector kernel up to M = 16), larger M the big-tile fp16
- * MFMA kernel.
+ * By default M = 1 runs the bandwidth-bound split-K vector kernel, 2 <= M <= 32 a small-batch
+ * MFMA kernel with the same split-K decomposition (when the format allows: no g_idx,
+ * group_size % 128 == 0; otherwise the vector kernel up to M = 16), larger M the big-tile fp16
+ * MFMA kernel (with K slices where the output tiles alone would not fill the chip).
  * Accumulation is in fp32; the result differs from the exact sum by fp32 reassociation
  * and the final fp16 rounding only.  The same inputs give bit-identical outputs on every
  * call (no floating point atomics are used).
@@ -150,9 +150,9 @@ GPTQ_API int gptq_w4a16_gemm_prepared(const void *x, const void *qweight_sorted,
 /*
  * Host-only: what gptq_w4a16_gemm_plan(..., request) would run for a problem of this shape.
  * `act_order` non-zero means a g_idx array would be passed; `request` may be NULL (automatic).
- * On success *resolved holds the kernel id (1, 2 or 3, never 0), its K split (1 for the big-tile MFMA
- * kernel) and its tile (vector and small-batch kernels: columns per workgroup; big-tile MFMA kernel:
- * tile id).  Touches no device.  Errors as for gptq_w4a16_gemm_plan's shape and plan checks.
+ * On success *resolved holds the kernel id (1, 2 or 3, never 0), its number of K slices and its tile
+ * (vector and small-batch kernels: columns per workgroup; big-tile MFMA kernel: tile id).  Touches no
+ * device.  Errors as for gptq_w4a16_gemm_plan's shape and plan checks.
  */
 GPTQ_API int gptq_w4a16_plan_query(int M, int K, int N, int group_size, int act_order,
                                    const gptq_w4a16_plan_t *request, gptq_w4a16_plan_t *resolved);
@@ -185,14 +185,14 @@ GPTQ_API int gptq_w4a16_unpack(const void *qweight, void *q_out, const void *qze
  * slices and one arrival counter per column tile.  gptq_w4a16_workspace_bytes() is an
  * upper bound for a given problem under the automatic plan, with or without g_idx (0 for invalid
  * shapes); an explicit plan that needs more fails with GPTQ_WORKSPACE_TOO_SMALL on a caller-owned
- * workspace.  If the caller never sets a
- * workspace the library allocates one with hipMalloc on first use and grows it when
- * needed (the only allocation it makes; growing synchronises the device).
- * gptq_w4a16_set_workspace() hands over caller-owned device memory (256-byte aligned, at
- * least gptq_w4a16_workspace_bytes() of the problems it will serve) instead; it clears the
- * memory with a synchronous hipMemset.  Passing NULL returns
- * to library-owned scratch.  There is one workspace per process: calls that overlap in
- * time on different streams race on it.
+ * workspace.  If the caller never sets a workspace the library allocates one with hipMalloc on
+ * first use and grows it when needed (the only allocation it makes besides the status word of
+ * gptq_w4a16_act_order_prepare; growing synchronises the device, so size it with one call before
+ * capturing a HIP graph).  gptq_w4a16_set_workspace() hands over caller-owned device memory
+ * (256-byte aligned, at least gptq_w4a16_workspace_bytes() of the problems it will serve)
+ * instead; it clears the memory with a synchronous hipMemset.  Passing NULL returns to
+ * library-owned scratch.  There is one workspace per device (the current one when the call is
+ * made): calls that overlap in time on different streams of one device race on it.
  */
 GPTQ_API size_t gptq_w4a16_workspace_bytes(int M, int K, int N, int group_size);
 GPTQ_API int gptq_w4a16_set_workspace(void *dev_ptr, size_t bytes);
