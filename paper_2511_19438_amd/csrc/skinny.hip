@@ -80,9 +80,10 @@ void skinny_make_plan(const Problem &p, SkinnyPlan &plan)
         // One workgroup per compute unit is the target (measured: 192..344 unsplit workgroups beat any split
         // of the same layer, and narrow layers want tiles * split = 256) - but the fp32 partial sums that the
         // slices exchange through scratch (8 bytes per slice and output: written once, read once) may not
-        // exceed a quarter of the packed weight bytes (K*N/2), or they, not the weights, set the time:
-        // split * M * N * 8 <= K * N / 8.  Slices are whole multiples of `quantum` units.
-        int max_split = p.K / (64 * launch_m);
+        // exceed half of the packed weight bytes (K*N/2), or they, not the weights, set the time:
+        // split * M * N * 8 <= K * N / 4 (measured on 4096x4096 at 24-32 rows: four slices 8.6-9.1 us, two
+        // slices 9.7-10.5).  Slices are whole multiples of `quantum` units.
+        int max_split = p.K / (32 * launch_m);
         if (max_split < 1)
             max_split = 1;
         int split = (256 + tiles_n / 2) / tiles_n;
