@@ -21,7 +21,8 @@ hipError_t launch_one(const Args &a, size_t lds_bytes, hipStream_t stream)
         if (err != hipSuccess)
             return err;
     }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.tiles_n * a.split_k)), dim3((ABL & kEightWaves) ? 512 : 256), lds_bytes, stream, a);
+    constexpr unsigned threads = (ABL & kEightWaves) ? 512 : 256;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.tiles_n * a.split_k)), dim3(threads), lds_bytes, stream, a);
     return hipGetLastError();
 }
 
