@@ -203,3 +203,26 @@ def test_shape_limits_of_the_32_bit_offsets(lib):
         assert e.value.code == -2
         assert lib.gptq_w4a16_workspace_bytes(1, K, N, 128) == 0
     assert binding.gptq_w4a16_plan_query(1, 1 << 19, 1 << 13, 128).kernel == 1
+
+
+def test_big_tile_plan_is_well_formed_for_every_shape(lib):
+    """The big-tile kernel's automatic plan names an existing tile, splits K only on the two small tiles, never
+    into more slices than 64-k stages, and its scratch is covered by the workspace bound wherever the default
+    dispatch would run it."""
+    from paper_2511_19438_amd import binding, workloads
+
+    tile_dims = {1: (256, 256), 3: (128, 128), 5: (64, 128), 8: (128, 256)}
+    shapes = [(s.K, s.N) for s in workloads.LLAMA_7B + workloads.LLAMA_70B] + [(128, 32), (512, 264), (4096, 11008)]
+    for (K, N) in shapes:
+        for M in (33, 48, 64, 100, 128, 256, 512, 2048, 5000):
+            pl = binding.gptq_w4a16_plan_query(M, K, N, 128, plan=binding.Plan(kernel=2))
+            assert pl.kernel == 2 and pl.tile in tile_dims, (M, K, N, pl.tile)
+            assert 1 <= pl.split_k <= max(1, K // 64)
+            assert pl.split_k == 1 or pl.tile in (3, 5), (M, K, N, pl.tile, pl.split_k)
+            if pl.split_k > 1 and binding.gptq_w4a16_plan_query(M, K, N, 128).kernel == 2:
+                bm, bn = tile_dims[pl.tile]
+                partial = pl.split_k * (-(-M // bm)) * (-(-N // bn)) * bm * bn * 4
+                assert lib.gptq_w4a16_workspace_bytes(M, K, N, 128) >= partial
+    # few output tiles and a deep K: slices; many tiles: none
+    assert binding.gptq_w4a16_plan_query(64, 11008, 4096, 128).split_k > 1
+    assert binding.gptq_w4a16_plan_query(2048, 4096, 22016, 128).split_k == 1
