@@ -61,7 +61,8 @@ enum gptq_status {
     GPTQ_UNSUPPORTED_SHAPE = -2,   /* divisibility rules above violated */
     GPTQ_MISALIGNED = -3,          /* a base pointer is not 16-byte aligned */
     GPTQ_HIP_ERROR = -4,           /* a HIP call or a kernel launch failed */
-    GPTQ_WORKSPACE_TOO_SMALL = -5  /* caller-set workspace smaller than gptq_w4a16_workspace_bytes() */
+    GPTQ_WORKSPACE_TOO_SMALL = -5, /* caller-set workspace smaller than gptq_w4a16_workspace_bytes() */
+    GPTQ_STATIC_SCRATCH_EXCEEDED = -6 /* gptq_w4a16_gemm_static: the problem needs more than the static scratch */
 };
 
 /*
@@ -80,6 +81,23 @@ enum gptq_status {
 GPTQ_API int gptq_w4a16_gemm(const void *x, const void *qweight, const void *qzeros, const void *scales,
                     const void *g_idx, void *out, int M, int K, int N, int group_size,
                     gptq_stream_t stream);
+
+/*
+ * gptq_w4a16_gemm for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same operation, arguments, kernels, automatic plan and (bit-identical)
+ * results as gptq_w4a16_gemm, but the split-K scratch (partial sums and arrival counters) is a fixed block of
+ * GPTQ_STATIC_SCRATCH_BYTES inside the library's device image: every GPU the library runs on holds it until the
+ * process ends, and the call makes no hipMalloc / hipFree and ignores gptq_w4a16_set_workspace().  A problem
+ * whose plan needs more scratch returns GPTQ_STATIC_SCRATCH_EXCEEDED and enqueues nothing (needs are at most
+ * 256 KiB + 4 * slices * M * N bytes; every Llama-7B/70B layer shape up to M = 2048 fits).  The first call on a
+ * device also enqueues one small kernel on `stream` that clears the arrival counters.  All calls on one GPU share
+ * the block: calls that overlap in time on one GPU (different streams) race, as do a call here and a graph replay
+ * that uses it.
+ */
+#define GPTQ_STATIC_SCRATCH_BYTES (32u << 20)
+GPTQ_API int gptq_w4a16_gemm_static(const void *x, const void *qweight, const void *qzeros, const void *scales,
+                                    const void *g_idx, void *out, int M, int K, int N, int group_size,
+                                    gptq_stream_t stream);
 
 /*
  * Launch plan for gptq_w4a16_gemm_plan(): selects the kernel and its decomposition

@@ -33,7 +33,7 @@ class Plan(ctypes.Structure):
                 ("flags", ctypes.c_int), ("reserved", ctypes.c_int * 4)]
 
 
-EXPORTS = ("gptq_w4a16_gemm", "gptq_w4a16_gemm_plan", "gptq_w4a16_plan_query", "gptq_w4a16_act_order_prepare",
+EXPORTS = ("gptq_w4a16_gemm", "gptq_w4a16_gemm_static", "gptq_w4a16_gemm_plan", "gptq_w4a16_plan_query", "gptq_w4a16_act_order_prepare",
            "gptq_w4a16_gemm_prepared", "gptq_w4a16_shift_zeros", "gptq_w4a16_dequant", "gptq_w4a16_unpack",
            "gptq_w4a16_workspace_bytes", "gptq_w4a16_set_workspace", "gptq_w4a16_strerror", "gptq_w4a16_version")
 
@@ -51,6 +51,8 @@ def load() -> ctypes.CDLL:
     vp, ci = ctypes.c_void_p, ctypes.c_int
     lib.gptq_w4a16_gemm.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, vp]
     lib.gptq_w4a16_gemm.restype = ci
+    lib.gptq_w4a16_gemm_static.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, vp]
+    lib.gptq_w4a16_gemm_static.restype = ci
     lib.gptq_w4a16_gemm_plan.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, vp, ctypes.POINTER(Plan)]
     lib.gptq_w4a16_gemm_plan.restype = ci
     lib.gptq_w4a16_plan_query.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(Plan), ctypes.POINTER(Plan)]
@@ -116,7 +118,13 @@ def _shapes(qweight, qzeros, scales, g_idx, group_size):
     return K, N
 
 
-def gptq_w4a16_gemm(x, qweight, qzeros, scales, g_idx, out, group_size: int, plan: Optional[Plan] = None):
+def gptq_w4a16_gemm_static(x, qweight, qzeros, scales, g_idx, out, group_size: int):
+    """gptq_w4a16_gemm on the library's static scratch block: allocates nothing (see the header)."""
+    return gptq_w4a16_gemm(x, qweight, qzeros, scales, g_idx, out, group_size, _static=True)
+
+
+def gptq_w4a16_gemm(x, qweight, qzeros, scales, g_idx, out, group_size: int, plan: Optional[Plan] = None,
+                    _static: bool = False):
     """out[M, N] = x[M, K] @ W (see the header).  Shapes are taken from the tensors; `out` is overwritten."""
     K, N = _shapes(qweight, qzeros, scales, g_idx, group_size)
     if x.dim() != 2 or x.shape[1] != K:
@@ -128,12 +136,14 @@ def gptq_w4a16_gemm(x, qweight, qzeros, scales, g_idx, out, group_size: int, pla
     args = (_ptr(x, torch.float16, "x"), _ptr(qweight, torch.int32, "qweight"), _ptr(qzeros, torch.int32, "qzeros"),
             _ptr(scales, torch.float16, "scales"), _ptr(g_idx, torch.int32, "g_idx"), _ptr(out, torch.float16, "out"),
             M, K, N, int(group_size), _stream())
-    if plan is None:
+    if _static:
+        rc = lib.gptq_w4a16_gemm_static(*args)
+    elif plan is None:
         rc = lib.gptq_w4a16_gemm(*args)
     else:
         rc = lib.gptq_w4a16_gemm_plan(*args, ctypes.byref(plan))
     if rc != 0:
-        raise GptqError(rc, "gptq_w4a16_gemm")
+        raise GptqError(rc, "gptq_w4a16_gemm_static" if _static else "gptq_w4a16_gemm")
     return out
 
 

@@ -23,6 +23,49 @@ struct Workspace {
 std::mutex g_mutex;
 Workspace g_ws[kMaxDevices];
 
+// Scratch of gptq_w4a16_gemm_static(): a fixed block in every device's copy of the code object, for callers
+// that may not allocate.  The array's name is only a host-side handle; its device address is looked up once
+// per device (static_scratch_ptr) and that pointer is what kernels and fills receive.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+void *g_static_ptr[kMaxDevices] = {};
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+__global__ void clear_words_kernel(unsigned *p, unsigned n)
+{
+    const unsigned i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n)
+        p[i] = 0u;
+}
+
+// Device address of the current device's static scratch.  The first call on a device looks the address up and
+// clears the arrival counters at its front with a small kernel on `stream` (a kernel, not a memset: the call
+// may be under stream capture).  No allocation.
+int static_scratch_ptr(hipStream_t stream, void **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return GPTQ_HIP_ERROR;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (!g_static_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr)
+            return GPTQ_HIP_ERROR;
+        const unsigned words = (unsigned)(decode_counter_bytes(0) / sizeof(unsigned));
+        hipLaunchKernelGGL(clear_words_kernel, dim3((words + 255) / 256), dim3(256), 0, stream,
+                           static_cast<unsigned *>(ptr), words);
+        if (hipGetLastError() != hipSuccess)
+            return GPTQ_HIP_ERROR;
+        g_static_ptr[dev] = ptr;
+    }
+    *out = g_static_ptr[dev];
+    return GPTQ_OK;
+}
+
 bool aligned16(const void *p)
 {
     return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
@@ -194,13 +237,9 @@ int check_plan(const gptq_w4a16_plan_t *plan)
     return GPTQ_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-int gptq_w4a16_gemm_plan(const void *x, const void *qweight, const void *qzeros, const void *scales,
-                         const void *g_idx, void *out, int M, int K, int N, int group_size,
-                         gptq_stream_t stream, const gptq_w4a16_plan_t *plan)
+// Validates the arguments of a GEMM call and fills `p`.
+int make_problem(const void *x, const void *qweight, const void *qzeros, const void *scales, const void *g_idx,
+                 void *out, int M, int K, int N, int group_size, const gptq_w4a16_plan_t *plan, Problem &p)
 {
     if (!x || !qweight || !qzeros || !scales || !out || M <= 0)
         return GPTQ_INVALID_ARG;
@@ -212,7 +251,6 @@ int gptq_w4a16_gemm_plan(const void *x, const void *qweight, const void *qzeros,
     if (!aligned16(x) || !aligned16(qweight) || !aligned16(qzeros) || !aligned16(scales) || !aligned16(out) ||
         (g_idx && !aligned16(g_idx)))
         return GPTQ_MISALIGNED;
-    Problem p;
     p.x = static_cast<const half_t *>(x);
     p.qweight = static_cast<const uint32_t *>(qweight);
     p.qzeros = static_cast<const uint32_t *>(qzeros);
@@ -225,7 +263,41 @@ int gptq_w4a16_gemm_plan(const void *x, const void *qweight, const void *qzeros,
     p.group_size = group_size;
     if (plan && (plan->flags & 7) != 0 && !decode_ablation_supported(p))
         return GPTQ_UNSUPPORTED_SHAPE;
+    return GPTQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gptq_w4a16_gemm_plan(const void *x, const void *qweight, const void *qzeros, const void *scales,
+                         const void *g_idx, void *out, int M, int K, int N, int group_size,
+                         gptq_stream_t stream, const gptq_w4a16_plan_t *plan)
+{
+    Problem p;
+    const int rc = make_problem(x, qweight, qzeros, scales, g_idx, out, M, K, N, group_size, plan, p);
+    if (rc != GPTQ_OK)
+        return rc;
     return run_gemm(p, static_cast<hipStream_t>(stream), plan);
+}
+
+int gptq_w4a16_gemm_static(const void *x, const void *qweight, const void *qzeros, const void *scales,
+                           const void *g_idx, void *out, int M, int K, int N, int group_size,
+                           gptq_stream_t stream)
+{
+    Problem p;
+    const int rc = make_problem(x, qweight, qzeros, scales, g_idx, out, M, K, N, group_size, nullptr, p);
+    if (rc != GPTQ_OK)
+        return rc;
+    const Resolved r = resolve(p, nullptr);
+    if (scratch_bytes(p, r) > kStaticScratchBytes)
+        return GPTQ_STATIC_SCRATCH_EXCEEDED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    void *ws = nullptr;
+    const int wrc = static_scratch_ptr(st, &ws);
+    if (wrc != GPTQ_OK)
+        return wrc;
+    return launch_resolved(p, r, ws, st);
 }
 
 int gptq_w4a16_gemm(const void *x, const void *qweight, const void *qzeros, const void *scales,
@@ -493,6 +565,8 @@ const char *gptq_w4a16_strerror(int code)
     case GPTQ_MISALIGNED: return "a base pointer is not 16-byte aligned";
     case GPTQ_HIP_ERROR: return "a HIP call or kernel launch failed";
     case GPTQ_WORKSPACE_TOO_SMALL: return "caller-set workspace is too small for this problem";
+    case GPTQ_STATIC_SCRATCH_EXCEEDED:
+        return "problem needs more split-K scratch than the 32 MiB static block of gptq_w4a16_gemm_static";
     default: return "unknown status code";
     }
 }

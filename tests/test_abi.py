@@ -27,11 +27,11 @@ def declared_functions():
 
 def test_header_declares_the_expected_entry_points():
     names = declared_functions()
-    assert len(names) == len(set(names)) == 12
+    assert len(names) == len(set(names)) == 13
     for required in ("gptq_w4a16_gemm", "gptq_w4a16_dequant", "gptq_w4a16_unpack", "gptq_w4a16_workspace_bytes",
                      "gptq_w4a16_set_workspace", "gptq_w4a16_strerror", "gptq_w4a16_version",
                      "gptq_w4a16_gemm_plan", "gptq_w4a16_plan_query", "gptq_w4a16_act_order_prepare",
-                     "gptq_w4a16_gemm_prepared", "gptq_w4a16_shift_zeros"):
+                     "gptq_w4a16_gemm_prepared", "gptq_w4a16_shift_zeros", "gptq_w4a16_gemm_static"):
         assert required in names
 
 
@@ -47,8 +47,8 @@ def test_library_exports_every_declared_symbol(lib):
 def test_status_strings(lib):
     from paper_2511_19438_amd import binding
 
-    texts = {binding.strerror(c) for c in (0, -1, -2, -3, -4, -5)}
-    assert len(texts) == 6
+    texts = {binding.strerror(c) for c in (0, -1, -2, -3, -4, -5, -6)}
+    assert len(texts) == 7
     assert "unknown" in binding.strerror(-99)
 
 
