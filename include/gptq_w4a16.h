@@ -140,8 +140,9 @@ GPTQ_API int gptq_w4a16_gemm_plan(const void *x, const void *qweight, const void
                          gptq_stream_t stream, const gptq_w4a16_plan_t *plan);
 
 /*
- * One-time repack of an act-order checkpoint (Section 2.1: with activation ordering, row k of the
- * weight belongs to group g_idx[k]; the map is fixed once the checkpoint is loaded).
+ * One-time repack of an act-order checkpoint (the paper does not treat activation ordering; it is part of
+ * the problem statement this library is built to: row k of the weight belongs to group g_idx[k], and the map
+ * is fixed once the checkpoint is loaded).
  * Writes perm int32[K] (device) = the stable order of k by g_idx[k], and qweight_sorted int32[K/8, N]
  * (device, same packing as qweight, must not alias it) whose row j is row perm[j] of qweight, so that
  * row j belongs to group j / group_size like a checkpoint without g_idx.  qzeros and scales are used
@@ -204,13 +205,19 @@ GPTQ_API int gptq_w4a16_unpack(const void *qweight, void *q_out, const void *qze
  * upper bound for a given problem under the automatic plan, with or without g_idx (0 for invalid
  * shapes); an explicit plan that needs more fails with GPTQ_WORKSPACE_TOO_SMALL on a caller-owned
  * workspace.  If the caller never sets a workspace the library allocates one with hipMalloc on
- * first use and grows it when needed (the only allocation it makes besides the status word of
- * gptq_w4a16_act_order_prepare; growing synchronises the device, so size it with one call before
- * capturing a HIP graph).  gptq_w4a16_set_workspace() hands over caller-owned device memory
- * (256-byte aligned, at least gptq_w4a16_workspace_bytes() of the problems it will serve)
- * instead; it clears the memory with a synchronous hipMemset.  Passing NULL returns to
- * library-owned scratch.  There is one workspace per device (the current one when the call is
- * made): calls that overlap in time on different streams of one device race on it.
+ * first use and replaces it by a larger one when a problem needs more (the only allocations it makes
+ * besides the status word of gptq_w4a16_act_order_prepare).  An outgrown block is retired, not freed:
+ * launches in flight and HIP graphs captured earlier keep working on it, so later growth never invalidates a
+ * captured graph.  Growth is refused (GPTQ_WORKSPACE_TOO_SMALL, nothing enqueued) while `stream` is being
+ * captured, since it allocates and clears memory: make one eager call of every problem a graph will hold
+ * before capturing it, or use gptq_w4a16_gemm_static.  A graph replay and an eager call that use different
+ * blocks do not share arrival counters; two pieces of work that share one block must not overlap in time.
+ * gptq_w4a16_set_workspace() hands over caller-owned device memory (256-byte aligned, at least
+ * gptq_w4a16_workspace_bytes() of the problems it will serve) instead; it synchronises the device, frees
+ * every library-owned block (current and retired: graphs captured on them must not be replayed afterwards)
+ * and clears the new memory with a synchronous hipMemset.  Passing NULL returns to library-owned scratch.
+ * There is one workspace per device (the current one when the call is made): calls that overlap in time on
+ * different streams of one device race on it.
  */
 GPTQ_API size_t gptq_w4a16_workspace_bytes(int M, int K, int N, int group_size);
 GPTQ_API int gptq_w4a16_set_workspace(void *dev_ptr, size_t bytes);

@@ -1,7 +1,7 @@
 // One-time repack of an act-order (g_idx) checkpoint and the activation gather that goes with it.
 //
-// With activation ordering (Section 2.1: the quantisation visits the input channels in order of
-// importance) row k of the packed weight belongs to group g_idx[k], an arbitrary map.  The kernels
+// With activation ordering (not treated by the paper; part of the problem statement: the quantiser visited
+// the input channels in order of importance) row k of the packed weight belongs to group g_idx[k], an arbitrary map.  The kernels
 // that read g_idx per row pay for it on every call.  The map is fixed once the checkpoint is loaded,
 // so the rows can be sorted by group ONCE: with perm = the stable order of k by g_idx[k], row j of the
 // sorted matrix is row perm[j] of the original, group j / group_size, and

@@ -84,7 +84,32 @@ double estimate_us(const Problem &p, const Derived &d, int cols_per_wg, int chun
     return t;
 }
 
+// LDS of one workgroup (must mirror the kernel's carve-up): the slice's activations, the per-chunk activation
+// sums of the factored arithmetic, the cross-wavefront reduction buffer and, with g_idx, the slice's group
+// numbers plus a (scale, zero) table of ALL groups for the tile's columns.
+size_t lds_bytes(const Problem &p, const DecodePlan &plan, int mb, int waves)
+{
+    const bool act = p.g_idx != nullptr;
+    const int mc = mb < 4 ? mb : 4;
+    const int ls = plan.chunks_per_slice * plan.chunk_rows * 8;
+    size_t lds = ((size_t)mb * ls * sizeof(half_t) + 15) & ~(size_t)15;
+    if (!act && mb < 8)
+        lds += ((size_t)mb * plan.chunks_per_slice * 2 * sizeof(float) + 15) & ~(size_t)15;
+    lds += (size_t)waves * mc * plan.cols_per_wg * sizeof(float);
+    if (act)
+        lds += (size_t)ls * sizeof(int) + (size_t)(p.K / p.group_size) * plan.cols_per_wg * sizeof(uint32_t);
+    return lds;
+}
+
 }  // namespace
+
+bool decode_plan_fits(const Problem &p, const DecodePlan &plan)
+{
+    const int mb = batch_template(p.M < 16 ? p.M : 16);
+    const Derived d = derive(p, plan.cols_per_wg, plan.chunk_rows);
+    const int waves = decode_waves(mb, p.g_idx != nullptr, plan.chunk_rows, (long long)d.tiles_n * plan.split_k);
+    return lds_bytes(p, plan, mb, waves) <= kMaxLdsBytes;
+}
 
 void decode_make_plan(const Problem &p, DecodePlan &plan)
 {
@@ -239,15 +264,8 @@ hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspa
         a.chunks_per_slice = plan.chunks_per_slice;
         a.total_chunks = d.total_chunks;
 
-        const int mc = mb < 4 ? mb : 4;
-        const int ls = plan.chunks_per_slice * plan.chunk_rows * 8;
-        size_t lds = ((size_t)mb * ls * sizeof(half_t) + 15) & ~(size_t)15;
-        if (!act && mb < 8)  // per-chunk sums of the activations (must mirror the kernel's carve-up)
-            lds += ((size_t)mb * plan.chunks_per_slice * 2 * sizeof(float) + 15) & ~(size_t)15;
         const int waves = decode_waves(mb, act, plan.chunk_rows, (long long)d.tiles_n * plan.split_k);
-        lds += (size_t)waves * mc * plan.cols_per_wg * sizeof(float);
-        if (act)
-            lds += (size_t)ls * sizeof(int) + (size_t)a.groups * plan.cols_per_wg * sizeof(uint32_t);
+        const size_t lds = lds_bytes(p, plan, mb, waves);
         if (lds > kMaxLdsBytes)
             return hipErrorInvalidValue;
 

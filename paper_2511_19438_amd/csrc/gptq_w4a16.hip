@@ -3,6 +3,7 @@
 #include "gptq_w4a16.h"
 
 #include <mutex>
+#include <vector>
 
 #include "kernels.h"
 
@@ -22,6 +23,7 @@ struct Workspace {
 
 std::mutex g_mutex;
 Workspace g_ws[kMaxDevices];
+std::vector<void *> g_retired[kMaxDevices];  // outgrown library-owned blocks, still referenced by earlier work
 
 // Scratch of gptq_w4a16_gemm_static(): a fixed block in every device's copy of the code object, for callers
 // that may not allocate.  The array's name is only a host-side handle; its device address is looked up once
@@ -86,7 +88,13 @@ int check_shape(int K, int N, int group_size)
 }
 
 // Makes sure the current device has scratch of at least `bytes`; returns it in *out.
-int acquire_workspace(size_t bytes, void **out)
+//
+// Library-owned scratch only ever grows, and a block that has been handed to a launch is never freed while the
+// library keeps its own scratch: launches still in flight and HIP graphs captured earlier hold its address (partial
+// sums, arrival counters, gathered activations).  A block that became too small is retired instead and stays
+// valid; retired blocks are released by gptq_w4a16_set_workspace().  Growth allocates and clears memory, which is
+// not allowed while `stream` is being captured: such a call is refused.
+int acquire_workspace(size_t bytes, hipStream_t stream, void **out)
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
@@ -99,13 +107,13 @@ int acquire_workspace(size_t bytes, void **out)
     }
     if (ws.ptr && !ws.owned)
         return GPTQ_WORKSPACE_TOO_SMALL;
-    // library-owned scratch: grow.  Earlier launches may still use the old block, so drain the device first.
-    if (ws.ptr) {
-        if (hipDeviceSynchronize() != hipSuccess)
-            return GPTQ_HIP_ERROR;
-        (void)hipFree(ws.ptr);
-        ws = Workspace();
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &capturing) != hipSuccess) {
+        (void)hipGetLastError();
+        return GPTQ_HIP_ERROR;
     }
+    if (capturing != hipStreamCaptureStatusNone)
+        return GPTQ_WORKSPACE_TOO_SMALL;
     size_t want = bytes + bytes / 2;
     if (want < (size_t)(8u << 20))
         want = (size_t)(8u << 20);
@@ -117,6 +125,8 @@ int acquire_workspace(size_t bytes, void **out)
         (void)hipFree(p);
         return GPTQ_HIP_ERROR;
     }
+    if (ws.ptr)
+        g_retired[dev].push_back(ws.ptr);
     ws.ptr = p;
     ws.bytes = want;
     ws.owned = true;
@@ -169,6 +179,13 @@ Resolved resolve(const Problem &p, const gptq_w4a16_plan_t *plan)
         r.decode.split_k = plan ? plan->split_k : 0;
         r.decode.flags = plan ? plan->flags : 0;
         decode_make_plan(p, r.decode);
+        if (!decode_plan_fits(p, r.decode)) {
+            // the big-tile kernel's general path takes any format at any M
+            r.kernel = kernel = 2;
+            r.prefill.tile = 0;
+            r.prefill.split_k = 0;
+            prefill_make_plan(p, r.prefill);
+        }
     } else if (kernel == 3) {
         r.skinny.cols_per_wg = plan ? plan->tile : 0;
         r.skinny.split_k = plan ? plan->split_k : 0;
@@ -208,7 +225,7 @@ int run_gemm(const Problem &p, hipStream_t stream, const gptq_w4a16_plan_t *plan
     void *ws = nullptr;
     const size_t bytes = scratch_bytes(p, r);
     if (bytes > 0) {
-        const int rc = acquire_workspace(bytes, &ws);
+        const int rc = acquire_workspace(bytes, stream, &ws);
         if (rc != GPTQ_OK)
             return rc;
     }
@@ -410,7 +427,7 @@ int gptq_w4a16_gemm_prepared(const void *x, const void *qweight_sorted, const vo
         void *ws = nullptr;
         const size_t bytes = scratch_bytes(p, r);
         if (bytes > 0) {
-            const int wrc = acquire_workspace(bytes, &ws);
+            const int wrc = acquire_workspace(bytes, st, &ws);
             if (wrc != GPTQ_OK)
                 return wrc;
         }
@@ -422,7 +439,7 @@ int gptq_w4a16_gemm_prepared(const void *x, const void *qweight_sorted, const vo
     if (kernel_bytes < decode_counter_bytes(N))
         kernel_bytes = decode_counter_bytes(N);
     void *ws = nullptr;
-    const int wrc = acquire_workspace(kernel_bytes + (size_t)M * K * sizeof(half_t), &ws);
+    const int wrc = acquire_workspace(kernel_bytes + (size_t)M * K * sizeof(half_t), st, &ws);
     if (wrc != GPTQ_OK)
         return wrc;
     half_t *xp = reinterpret_cast<half_t *>(static_cast<unsigned char *>(ws) + kernel_bytes);
@@ -538,10 +555,15 @@ int gptq_w4a16_set_workspace(void *dev_ptr, size_t bytes)
         return GPTQ_WORKSPACE_TOO_SMALL;  // not even room for the arrival counters
     std::lock_guard<std::mutex> lock(g_mutex);
     Workspace &ws = g_ws[dev];
-    if (ws.ptr && ws.owned) {
+    // the library's own blocks, current and retired, go now: drain the device first
+    if ((ws.ptr && ws.owned) || !g_retired[dev].empty()) {
         if (hipDeviceSynchronize() != hipSuccess)
             return GPTQ_HIP_ERROR;
-        (void)hipFree(ws.ptr);
+        if (ws.ptr && ws.owned)
+            (void)hipFree(ws.ptr);
+        for (void *old : g_retired[dev])
+            (void)hipFree(old);
+        g_retired[dev].clear();
     }
     ws = Workspace();
     if (dev_ptr) {

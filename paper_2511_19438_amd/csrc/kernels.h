@@ -54,6 +54,9 @@ void decode_make_plan(const Problem &p, DecodePlan &plan);
 size_t decode_workspace_bytes(const Problem &p, const DecodePlan &plan);
 size_t decode_counter_bytes(int N);
 hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspace, hipStream_t stream);
+// Whether a workgroup of the planned launch fits the LDS (the act-order variant keeps a table of every group
+// there, which very deep layers with small groups overflow).
+bool decode_plan_fits(const Problem &p, const DecodePlan &plan);
 // Whether the ablation variants of the vector kernel (DecodePlan::flags != 0) exist for this problem.
 bool decode_ablation_supported(const Problem &p);
 

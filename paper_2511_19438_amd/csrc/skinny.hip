@@ -69,7 +69,7 @@ void skinny_make_plan(const Problem &p, SkinnyPlan &plan)
     }
     // where the activations of a slice are staged in LDS (wide tiles, more than 32 rows) they must fit
     const bool direct = plan.cols_per_wg == 64;
-    int max_units = direct ? total_units : kMaxActivationLdsBytes / (rows * 2 + 8) / skinny::kUnitK;
+    int max_units = direct ? total_units : kMaxActivationLdsBytes / (rows * 2) / skinny::kUnitK;
     if (max_units < 1)
         max_units = 1;
     const int tiles_n = ceil_div(p.N, plan.cols_per_wg);
@@ -143,9 +143,7 @@ hipError_t launch_skinny(const Problem &p, const SkinnyPlan &plan, void *workspa
         const int rows = 16 * tm;
         // 64-column workgroups read the activations straight from global memory
         const bool direct = wn == 1;
-        const size_t xs = direct ? 0
-                                 : (size_t)rows * plan.units_per_slice * skinny::kUnitK * sizeof(half_t)  // activations
-                                       + (size_t)rows * plan.units_per_slice * 8;                        // and their sums
+        const size_t xs = direct ? 0 : (size_t)rows * plan.units_per_slice * skinny::kUnitK * sizeof(half_t);
         const int waves = waves_of(a.tiles_n, a.split_k, wn);
         const size_t red = (size_t)waves * rows * skinny::kCols * sizeof(float);  // [waves/wn][rows][64*wn]
         const size_t lds = xs > red ? xs : red;

@@ -201,40 +201,6 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
         __syncthreads();
     }
 
-    // ---- per (unit, row): S = sum of the unit's 128 activations and S_odd = the sum over odd k, by MFMA
-    //      against a constant operand (column 0: ones, column 1: ones at odd k), each split into an fp16
-    //      high and low part (22 significant bits) and kept in LDS as four halves
-    //      [S_hi, S_lo, S_odd_hi, S_odd_lo] for the correction step of the main loop ----
-    uint2 *xc = reinterpret_cast<uint2 *>(smem + (size_t)ROWS * Ls * sizeof(half_t));  // [nunits][ROWS]
-    if (!DIRECT) {
-        const uint32_t ones = cq == 0 ? 0x3C003C00u : (cq == 1 ? 0x3C000000u : 0u);
-        const half8_t bsum = __builtin_bit_cast(half8_t, u32x4_t{ones, ones, ones, ones});
-        for (int idx = wave; idx < nunits * TM; idx += kWaves) {
-            const int j = idx / TM;
-            const int i = idx - j * TM;
-            const int m = 16 * i + cq;
-            float4_t d = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                const int c = (j * 4 + st) * 4 + kg;
-                const int pc = (c & ~15) | ((c ^ m) & 15);
-                const half8_t av = *reinterpret_cast<const half8_t *>(xs + (size_t)m * Ls + pc * 8);
-                d = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bsum, d, 0, 0, 0);
-            }
-            if (cq < 2) {
-                uint32_t *dst = reinterpret_cast<uint32_t *>(xc + (size_t)j * ROWS + 16 * i + 4 * kg) + cq;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const half_t hi = (half_t)d[r];
-                    const half_t lo = (half_t)(d[r] - (float)hi);
-                    dst[2 * r] = (uint32_t)__builtin_bit_cast(uint16_t, hi) |
-                                 ((uint32_t)__builtin_bit_cast(uint16_t, lo) << 16);
-                }
-            }
-        }
-        __syncthreads();
-    }
-
     float4_t acc[TM][4];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -246,33 +212,28 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
 
     // One unit: 128 k of this lane's four columns against all batch rows.
     //
-    // The B operand is the biased code, not the weight: a pair of nibbles four k apart is masked out of the
-    // packed word and OR-ed into the mantissa of 1024.0 (even k) or 64.0 (odd k), five vector operations
-    // per packed word instead of sixteen for exact per-element weights.  The MFMA chain of the unit then
-    // holds sum_k x_k (bias_k + q_k); one more MFMA per n-block subtracts sum_k x_k (bias_k + z), written as
-    // (1024 + z) S - 960 S_odd with the staged sums as A operand, and the group's scale is applied to the
-    // chain's result in fp32:  acc += s * sum_k x_k (q_k - z).
-    // DIRECT: constant B operand of the sums, in the operand's k order (0,4) (1,5) (2,6) (3,7):
-    // column 0 adds all k, column 1 the odd ones
-    const uint32_t ones_even = cq == 0 ? 0x3C003C00u : 0u;
-    const uint32_t ones_odd = cq <= 1 ? 0x3C003C00u : 0u;
-    const half8_t bsum = __builtin_bit_cast(half8_t, u32x4_t{ones_even, ones_odd, ones_even, ones_odd});
-
+    // The B operand is the exact integer q - z, not the weight: a pair of nibbles four k apart is masked out of
+    // the packed word and OR-ed into the mantissa of 1024.0 (even k) or 64.0 (odd k), and one packed fp16 add of
+    // -(1024 + z) or -(64 + z) leaves q - z (exact: small integers).  Nine vector operations per packed word
+    // instead of sixteen for per-element weights; the group's scale is applied to the MFMA chain's result in
+    // fp32:  acc += s * sum_k x_k (q_k - z).  (Contracting the biased codes and cancelling sum_k x_k * bias
+    // afterwards saves the adds but loses digits to the size of that sum: activations with a common offset of a
+    // few tens then leave the tolerance band.)
     auto consume = [&](int u, const Regs &r) {
         const int j = u - u0;
-        uint32_t cz[4];
-        float sf[4], zf[4];
+        half2_t neg_lo[4], neg_hi[4];
+        float sf[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const uint32_t z = (r.zb >> (zshift + 4 * t)) & 15u;
-            cz[t] = 0xE400E400u | (z * 0x00010001u);  // (-(1024 + z), -(1024 + z))
-            zf[t] = -1024.f - (float)z;
+            const uint32_t zz = z | (z << 16);
+            neg_lo[t] = as_half2(zz | 0xE400E400u);         // (-(1024 + z)) x2
+            neg_hi[t] = as_half2((zz << 4) | 0xD400D400u);  // (-(64 + z)) x2
             const uint32_t pair = t < 2 ? r.sc.x : r.sc.y;
             const uint16_t sb = (uint16_t)((t & 1) ? (pair >> 16) : (pair & 0xffffu));
             sf[t] = (float)__builtin_bit_cast(half_t, sb);
         }
         float4_t d[TM][4];
-        float4_t dsum[TM];
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
             const uint32_t w[4] = {r.w[st].x, r.w[st].y, r.w[st].z, r.w[st].w};
@@ -281,9 +242,11 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
             for (int t = 0; t < 4; ++t) {
                 const uint32_t w8 = w[t] >> 8;
                 // k order inside the operand: (0,4) (1,5) (2,6) (3,7)
-                const u32x4_t codes = {(w[t] & magic.mask_lo) | magic.bias_lo, (w[t] & magic.mask_hi) | magic.bias_hi,
-                                       (w8 & magic.mask_lo) | magic.bias_lo, (w8 & magic.mask_hi) | magic.bias_hi};
-                b[t] = __builtin_bit_cast(half8_t, codes);
+                const half2_t c0 = as_half2((w[t] & magic.mask_lo) | magic.bias_lo) + neg_lo[t];
+                const half2_t c1 = as_half2((w[t] & magic.mask_hi) | magic.bias_hi) + neg_hi[t];
+                const half2_t c2 = as_half2((w8 & magic.mask_lo) | magic.bias_lo) + neg_lo[t];
+                const half2_t c3 = as_half2((w8 & magic.mask_hi) | magic.bias_hi) + neg_hi[t];
+                b[t] = half8_t{c0[0], c0[1], c1[0], c1[1], c2[0], c2[1], c3[0], c3[1]};
             }
             const int c = (j * 4 + st) * 4 + kg;  // 16-byte chunk of the activation row
 #pragma unroll
@@ -306,44 +269,15 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
                     d[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b[t], st == 0 ? zero : d[i][t], 0, 0, 0);
-                if (DIRECT)
-                    dsum[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bsum, st == 0 ? zero : dsum[i], 0, 0, 0);
             }
         }
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            if (DIRECT) {
-                // S and S_odd of row 4*kg + r sit in lanes 0 and 1 of this lane's row of sixteen: broadcast them
-                // (DPP row_share) and take the bias and the zero point off in fp32
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int rr = 0; rr < 4; ++rr) {
-                    const float sums = dsum[i][rr];  // (a bit_cast applied to the subscript itself reads element 0)
-                    const int bits = __float_as_int(sums);
-                    const float S = __int_as_float(__builtin_amdgcn_update_dpp(0, bits, 0x150, 0xf, 0xf, false));
-                    const float So = __int_as_float(__builtin_amdgcn_update_dpp(0, bits, 0x151, 0xf, 0xf, false));
-                    const float so960 = 960.f * So;
+            for (int t = 0; t < 4; ++t)
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const float v = __builtin_fmaf(zf[t], S, d[i][t][rr]) + so960;  // sum_k x_k (q_k - z)
-                        acc[i][t][rr] = __builtin_fmaf(sf[t], v, acc[i][t][rr]);
-                    }
-                }
-            } else {
-                uint2 sums = xc[(size_t)j * ROWS + 16 * i + cq];
-                if (kg != 0)
-                    sums = make_uint2(0u, 0u);  // the correction occupies the first four k slots only
-                const half8_t av = __builtin_bit_cast(half8_t, u32x4_t{sums.x, sums.y, 0u, 0u});
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const half8_t bv =
-                        __builtin_bit_cast(half8_t, u32x4_t{cz[t], 0x63806380u /* (960, 960) */, 0u, 0u});
-                    d[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, d[i][t], 0, 0, 0);
-#pragma unroll
-                    for (int rr = 0; rr < 4; ++rr)
-                        acc[i][t][rr] = __builtin_fmaf(sf[t], d[i][t][rr], acc[i][t][rr]);
-                }
-            }
-        }
+                for (int rr = 0; rr < 4; ++rr)
+                    acc[i][t][rr] = __builtin_fmaf(sf[t], d[i][t][rr], acc[i][t][rr]);
     };
 
     if (active) {

@@ -137,6 +137,10 @@ def test_vector_plan_is_well_formed_for_every_shape(lib):
         for M in (1, 2, 4, 8, 16):
             for act in (False, True):
                 pl = binding.gptq_w4a16_plan_query(M, K, N, 128, act_order=act, plan=binding.Plan(kernel=1))
+                if act and M >= 8 and K // 128 >= 512:
+                    # the act-order table of all groups plus the staged rows exceed the LDS: big-tile kernel instead
+                    assert pl.kernel == 2
+                    continue
                 assert pl.kernel == 1
                 assert pl.tile in (32, 64, 128, 256) and (not act or pl.tile == 64)
                 chunks = K // 32

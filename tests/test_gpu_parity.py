@@ -324,13 +324,13 @@ def test_codes_equal_to_zero_points_give_zero(B, M):
             "scales": np.full((K // group, N), 0.01, np.float16), "g_idx": None,
             "x": workloads.make_activations(M, K, seed=4)}
     out = run_gemm(B, case, group)
-    if M > 64:
-        # per-element dequantisation (big-tile MFMA kernel): every weight is exactly zero
+    if M > 1:
+        # exact q - z before the contraction (small-batch and big-tile MFMA kernels): every product is exactly zero
         assert np.all(out == 0)
     else:
-        # the small-batch kernels contract the biased codes (1024 + q) and take the bias and the zero point
-        # off per group in fp32: the cancellation leaves fp32 rounding noise of the order 1e-3 * scale, far
-        # inside the tolerance band around a reference of exactly zero
+        # the single-row vector kernel contracts the biased codes (1024 + q) and takes the bias and the zero
+        # point off per 32-k chunk in fp32: the cancellation leaves fp32 rounding noise of the order
+        # 1e-3 * scale, far inside the tolerance band around a reference of exactly zero
         assert np.all(np.abs(out.astype(np.float64)) <= 1e-3)
 
 
@@ -537,3 +537,130 @@ def test_graph_replays_match_eager(B, M, K, N, plan_args):
             got = out.cpu().numpy()
             assert np.array_equal(got.view(np.uint16), eager.view(np.uint16)), f"replay {rep} differs from eager"
             run_gemm(B, other, group, B.Plan(kernel=1, split_k=2, tile=64))  # eager work between the replays
+
+
+def test_captured_graph_survives_scratch_growth(B):
+    """A graph captured on library-owned scratch keeps replaying correctly after a larger eager problem has made
+    the library move to a bigger block (the outgrown block is retired, not freed)."""
+    group = 128
+    B.gptq_w4a16_set_workspace(None)  # back to a fresh library-owned block of minimum size (8 MiB)
+    small = workloads.make_case(1, 11008, 4096, group, seed=31)
+    assert B.gptq_w4a16_plan_query(1, 11008, 4096, group).split_k > 1
+    eager = run_gemm(B, small, group)
+    x, qw, qz, sc = (dev(small[k]) for k in ("x", "qweight", "qzeros", "scales"))
+    out = torch.zeros((1, 4096), dtype=torch.float16, device="cuda")
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            B.gptq_w4a16_gemm(x, qw, qz, sc, None, out, group)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy().view(np.uint16), eager.view(np.uint16))
+        # 5 K slices x 96 tiles x 64 x 128 fp32 = 15.7 MB of partial sums: more than the first block holds
+        big_plan = B.gptq_w4a16_plan_query(64, 4096, 12288, group)
+        assert big_plan.kernel == 2 and big_plan.split_k * 96 * 64 * 128 * 4 > 8 << 20
+        big = workloads.make_case(64, 4096, 12288, group, seed=32)
+        run_gemm(B, big, group)
+        junk = torch.full((16 << 20,), -1, dtype=torch.int32, device="cuda")  # would land in a freed block
+        for rep in range(3):
+            out.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy().view(np.uint16), eager.view(np.uint16)), f"replay {rep} after growth"
+            run_gemm(B, big, group)
+        del junk
+
+
+def test_scratch_growth_is_refused_under_capture(B):
+    group = 128
+    B.gptq_w4a16_set_workspace(None)
+    run_gemm(B, workloads.make_case(1, 1024, 264, group, seed=1), group)  # first block: 8 MiB
+    big = workloads.make_case(64, 4096, 12288, group, seed=32)
+    x, qw, qz, sc = (dev(big[k]) for k in ("x", "qweight", "qzeros", "scales"))
+    out = torch.zeros((64, 12288), dtype=torch.float16, device="cuda")
+    stream = torch.cuda.Stream()
+    code = None
+    with torch.cuda.stream(stream):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            out.zero_()
+            try:
+                B.gptq_w4a16_gemm(x, qw, qz, sc, None, out, group)
+            except B.GptqError as e:
+                code = e.code
+        torch.cuda.synchronize()
+    assert code == -5, "growing the scratch while the stream is captured must be refused"
+    got = run_gemm(B, big, group)  # eagerly it grows and works
+    rng = np.random.default_rng(3)
+    mi = rng.integers(0, 64, 256).astype(np.int32)
+    ni = rng.integers(0, 12288, 256).astype(np.int32)
+    ref = oracle.gemm_ref_sampled(big["x"], big["qweight"], big["qzeros"], big["scales"], None, group, mi, ni)
+    assert_within_band(got[mi, ni], ref, "after the refused capture")
+
+
+def test_act_order_table_too_large_for_lds_falls_back(B):
+    """896 groups x 64 columns of (scale, zero) do not fit the vector kernel's LDS: the call must not fail."""
+    M, K, N, group = 2, 28672, 64, 32
+    assert B.gptq_w4a16_plan_query(M, K, N, group, True).kernel == 2
+    case = workloads.make_case(M, K, N, group, seed=5, act_order=True)
+    out = run_gemm(B, case, group)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], case["g_idx"], group)
+    assert_within_band(out, ref, "act-order, 896 groups")
+
+
+@pytest.mark.parametrize("M,K,N,plan_args", [
+    (1, 4096, 520, dict(kernel=1)),
+    (4, 4096, 520, dict(kernel=1)),
+    (1, 4096, 520, dict(kernel=1, flags=8)),
+    (8, 4096, 520, dict(kernel=1)),
+    (8, 4096, 520, dict(kernel=3, tile=64)),
+    (24, 4096, 520, dict(kernel=3, tile=64, split_k=4)),
+    (8, 2048, 1024, dict(kernel=3, tile=256)),
+    (32, 2048, 1024, dict(kernel=3, tile=256, split_k=2)),
+    (96, 2048, 520, dict(kernel=2)),
+])
+@pytest.mark.parametrize("kind", ["offset", "outliers", "huge_offset"])
+def test_activations_with_large_mean_and_outliers(B, M, K, N, plan_args, kind):
+    """Activations with a large common offset or with outliers.
+
+    Two things happen then.  (1) The kernels that apply the group's scale AFTER the contraction (vector kernel
+    below eight rows, small-batch kernel) compute sum_k x_k * s * (q_k - z) with the unrounded product, the others
+    with the fp16-rounded weight of the dequant definition; the two differ by sum_k x_k * delta_k (delta = the fp16
+    rounding error of a weight), which is noise for zero-mean activations and adds up coherently under a common
+    offset: each kernel is held to the band around ITS definition of W, both computed here in fp64 from the
+    oracle's unpacked fields, and within 3 bands of the other one.  (2) The vector kernel below eight rows
+    contracts biased codes and cancels sum_k x_k * bias in fp32, which costs digits in proportion to the 32-k
+    sums of x: it is held to offsets of a few tens (the last case, sums of ~20000, is for the other kernels).
+    """
+    group = 128
+    scale_after = plan_args["kernel"] == 3 or (plan_args["kernel"] == 1 and M < 8)
+    if kind == "huge_offset" and plan_args["kernel"] == 1 and M < 8:
+        pytest.skip("beyond the documented input range of the biased-code arithmetic")
+    case = workloads.make_case(M, K, N, group, seed=11 * M + len(kind))
+    rng = np.random.default_rng(M + K)
+    x = case["x"].astype(np.float32)
+    if kind == "offset":
+        x = x + 40.0
+    elif kind == "outliers":
+        mask = rng.random(x.shape) < 0.01
+        x = np.where(mask, np.sign(x) * rng.uniform(50.0, 100.0, x.shape), x)
+    else:
+        x = x * 4.0 + 600.0  # every 128-k sum of x is ~77000: beyond fp16
+    case["x"] = x.astype(np.float16)
+    out = run_gemm(B, case, group, B.Plan(**plan_args)).astype(np.float64)
+    ref_rounded = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    q = oracle.unpack_qweight(case["qweight"]).astype(np.float64)
+    z = np.repeat(oracle.unpack_qzeros(case["qzeros"]).astype(np.float64), group, axis=0)
+    w_exact = (q - z) * np.repeat(case["scales"].astype(np.float64), group, axis=0)
+    ref_exact = case["x"].astype(np.float64) @ w_exact
+    own, other = (ref_exact, ref_rounded) if scale_after else (ref_rounded, ref_exact)
+    finite = np.abs(ref_rounded) < 60000.0  # outputs beyond fp16 range are not comparable
+    assert finite.mean() > 0.9
+
+    def worst(ref):
+        return float((np.abs(out - ref)[finite] / (TOL * np.maximum(1.0, np.abs(ref[finite])))).max())
+
+    assert worst(own) <= 0.5, f"{kind}: err/tol = {worst(own):.3f} against the kernel's own definition of W"
+    if kind != "huge_offset":
+        assert worst(other) <= 8.0, f"{kind}: err/tol = {worst(other):.3f} against the other definition of W"
