@@ -51,7 +51,8 @@ def main():
     ap.add_argument("--no-context", action="store_true", help="skip the device-copy / dense-matmul context lines")
     ap.add_argument("--no-sweep", action="store_true", help="skip the batch-size / act-order / 70B side tables")
     ap.add_argument("--ablation", action="store_true",
-                    help="also time the vector kernel with each of the paper's three techniques taken out")
+                    help="time the vector kernel with each of the paper's three techniques taken out (part of the "
+                         "default run; this switch keeps it when --no-sweep drops the other side tables)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference kernel for the HBM traffic counters)")
     args = ap.parse_args()
@@ -175,6 +176,16 @@ def main():
                "kind": "oracle",
                "sample": f"layer 0 of the step (4 GEMVs, {layer_bytes / 1e6:.1f} MB algorithmic), {reps} repetitions, "
                          f"{spent:.1f} s"}
+        # the prefill half of the metric on the same cores: a row sample of the M = 2048 problem on the qkv shape
+        rows = 16
+        c = host_layer0[0]
+        xs = workloads.make_activations(2048, shapes[0].K, seed=workloads.case_seed(3, 0))[:rows]
+        t = time.perf_counter()
+        oracle.gemm_ref(xs, c["qweight"], c["qzeros"], c["scales"], None, GROUP)
+        dt = time.perf_counter() - t
+        cpu["prefill"] = {"value": round(2.0 * rows * shapes[0].K * shapes[0].N / dt / 1e9, 2), "unit": "GFLOP/s",
+                          "sample": f"{rows} of the 2048 rows of M=2048 K={shapes[0].K} N={shapes[0].N} "
+                                    f"(all columns), {dt:.1f} s; the full problem would take {dt * 2048 / rows:.0f} s"}
 
     line = {
         "metric": "W4A16 GEMM: HBM GB/s at M=1 decode; TFLOP/s at M=2048 prefill",
@@ -194,10 +205,10 @@ def main():
         line["roofline_prefill"] = prefill["roofline"]
     if not args.no_sweep:
         line["sweep"] = sweep_tables(torch, B, workloads, layers)
-    if args.ablation:
+    if args.ablation or not args.no_sweep:
         line["ablation"] = ablation_table(torch, B, workloads, layers)
     if not args.no_context:
-        line["context"] = context_lines(torch)
+        line["context"] = context_lines(torch, B)
     print(json.dumps(line))
 
 
@@ -226,10 +237,16 @@ def graph_us(torch, launches, reps=6):
 
 def sweep_tables(torch, B, workloads, layers):
     """Side tables (not the headline): the decode and mid batch sweep on the Llama-7B shapes, the act-order layer with
-    its g_idx kernels and repacked, and single-row GEMVs on the Llama-70B shapes.  Every launch streams its
-    weights from HBM (the launches of a graph rotate over distinct weight copies larger than the caches)."""
+    its g_idx kernels and repacked, and the Llama-70B shapes at M = 1 and 16.  Every launch streams its weights from
+    HBM (the launches of a graph rotate over distinct weight copies larger than the caches).  Per shape also:
+    `read_probe`, a plain read kernel over the same packed-weight buffers timed the same way (what any kernel of
+    that footprint pays for launch, latency and ramp), and `vector_dot`, the single-row kernel with its inner loop
+    on the vector ALU only (v_dot2_f32_f16) instead of 4x4x4 MFMAs."""
     shapes = workloads.LLAMA_7B
-    out = {"unit": "us per launch (GB/s of algorithmic bytes)", "llama7b": [], "act_order": [], "llama70b": []}
+    out = {"unit": "us per launch (GB/s of algorithmic bytes[, fraction of the 8 TB/s peak])", "llama7b": [],
+           "act_order": [], "llama70b": []}
+    sink = torch.zeros(256, dtype=torch.int32, device="cuda")
+    vdot = B.Plan(kernel=1, flags=8)
     for si, sh in enumerate(shapes):
         row = {"shape": f"{sh.name} K={sh.K} N={sh.N}"}
         for M in workloads.DECODE_BATCHES + workloads.MID_BATCHES:
@@ -238,23 +255,24 @@ def sweep_tables(torch, B, workloads, layers):
             fns = [(lambda t=mats[si]: B.gptq_w4a16_gemm(x, t["qweight"], t["qzeros"], t["scales"], None, o, GROUP))
                    for mats in layers]
             us = graph_us(torch, fns)
-            row[f"M={M}"] = [round(us, 2), round(algorithmic_bytes(M, sh.K, sh.N) / us / 1e3)]
+            gbs = algorithmic_bytes(M, sh.K, sh.N) / us / 1e3
+            row[f"M={M}"] = [round(us, 2), round(gbs), round(gbs / HBM_PEAK_GBS, 3)]
+        x = torch.randn((1, sh.K), device="cuda").half()
+        o = torch.empty((1, sh.N), dtype=torch.float16, device="cuda")
+        us = graph_us(torch, [(lambda t=mats[si]: B.gptq_w4a16_gemm(x, t["qweight"], t["qzeros"], t["scales"], None, o,
+                                                                    GROUP, vdot)) for mats in layers])
+        row["vector_dot M=1"] = [round(us, 2), round(algorithmic_bytes(1, sh.K, sh.N) / us / 1e3)]
+        us = graph_us(torch, [(lambda t=mats[si]: B.gptq_w4a16_stream_probe(t["qweight"], sink)) for mats in layers])
+        row["read_probe"] = [round(us, 2), round(sh.K * sh.N // 2 / us / 1e3)]
         out["llama7b"].append(row)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(1234)
-
-    def device_weights(K, N, copies):
-        qws = [torch.randint(-2**31, 2**31 - 1, (K // 8, N), dtype=torch.int32, device="cuda", generator=gen)
-               for _ in range(copies)]
-        qz = torch.randint(-2**31, 2**31 - 1, (K // GROUP, N // 8), dtype=torch.int32, device="cuda", generator=gen)
-        sc = (torch.rand((K // GROUP, N), device="cuda", generator=gen) * 0.009 + 0.001).half()
-        return qws, qz, sc
 
     # act-order layer (rows of a group scattered over K): the kernels that look g_idx up per row, and the same
     # layer after the one-time repack
     sh = workloads.ACT_ORDER_SHAPE
     copies = 24
-    qws, qz, sc = device_weights(sh.K, sh.N, copies)
+    qws, qz, sc = device_weights(torch, sh.K, sh.N, copies, gen)
     g_idx = (torch.randperm(sh.K, device="cuda", generator=gen) // GROUP).int()
     sorted_qws = [torch.empty_like(q) for q in qws]
     perm = torch.empty(sh.K, dtype=torch.int32, device="cuda")
@@ -265,14 +283,16 @@ def sweep_tables(torch, B, workloads, layers):
         o = torch.empty((M, sh.N), dtype=torch.float16, device="cuda")
         a = graph_us(torch, [(lambda q=q: B.gptq_w4a16_gemm(x, q, qz, sc, g_idx, o, GROUP)) for q in qws])
         b = graph_us(torch, [(lambda q=q: B.gptq_w4a16_gemm_prepared(x, q, qz, sc, perm, o, GROUP)) for q in sorted_qws])
+        c = graph_us(torch, [(lambda q=q: B.gptq_w4a16_gemm(x, q, qz, sc, None, o, GROUP)) for q in qws])
         nbytes = algorithmic_bytes(M, sh.K, sh.N, act_order=True)
         out["act_order"].append({"shape": f"K={sh.K} N={sh.N} M={M}", "g_idx_kernel": [round(a, 2), round(nbytes / a / 1e3)],
-                                 "repacked": [round(b, 2), round(nbytes / b / 1e3)]})
+                                 "repacked": [round(b, 2), round(nbytes / b / 1e3)],
+                                 "plain_format_same_shape": [round(c, 2), round(nbytes / c / 1e3)]})
     del qws, sorted_qws
     torch.cuda.empty_cache()
     for sh in workloads.LLAMA_70B:
         copies = max(2, int(1.3e9 // (sh.K * sh.N // 2)) + 1)
-        qws, qz, sc = device_weights(sh.K, sh.N, copies)
+        qws, qz, sc = device_weights(torch, sh.K, sh.N, copies, gen)
         row = {"shape": f"{sh.name} K={sh.K} N={sh.N}"}
         for M in (1, 16):
             x = torch.randn((M, sh.K), device="cuda").half()
@@ -280,6 +300,8 @@ def sweep_tables(torch, B, workloads, layers):
             us = graph_us(torch, [(lambda q=q: B.gptq_w4a16_gemm(x, q, qz, sc, None, o, GROUP)) for q in qws])
             gbs = algorithmic_bytes(M, sh.K, sh.N) / us / 1e3
             row[f"M={M}"] = [round(us, 2), round(gbs), round(gbs / HBM_PEAK_GBS, 3)]
+        us = graph_us(torch, [(lambda q=q: B.gptq_w4a16_stream_probe(q, sink)) for q in qws])
+        row["read_probe"] = [round(us, 2), round(sh.K * sh.N // 2 / us / 1e3)]
         out["llama70b"].append(row)
         del qws
         torch.cuda.empty_cache()
@@ -314,33 +336,31 @@ def measured_traffic(key):
         return None
 
 
-def context_lines(torch, reps=10):
-    """What the box itself achieves: a device copy and a dense fp16 matmul, as context for the roofline fractions."""
+def context_lines(torch, B):
+    """What the box itself achieves, as context for the roofline fractions: a device copy, the dense fp16 matmul of
+    the vendor library on the prefill shape, and the matrix pipe alone (MFMA-only loop on random register operands,
+    no memory traffic) under the same power budget."""
     n = 256 * 1024 * 1024
     src = torch.empty(n, dtype=torch.int32, device="cuda").random_()
     dst = torch.empty_like(src)
-    dst.copy_(src)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(reps):
-        dst.copy_(src)
-    e1.record()
-    torch.cuda.synchronize()
-    copy_gbs = 2.0 * n * 4 * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    sec = timed_launches(torch, lambda: dst.copy_(src), min_warm_s=0.02, min_timed_s=0.02)
+    copy_gbs = 2.0 * n * 4 / sec / 1e9
     del src, dst
     M, K, N = 2048, 4096, 22016
     x = torch.randn((M, K), device="cuda").half()
     w = torch.randn((K, N), device="cuda").half()
-    for _ in range(3):
-        torch.matmul(x, w)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(reps):
-        torch.matmul(x, w)
-    e1.record()
-    torch.cuda.synchronize()
-    dense = 2.0 * M * K * N * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    sec = timed_launches(torch, lambda: torch.matmul(x, w))
+    dense = 2.0 * M * K * N / sec / 1e12
+    del x, w
+    ops = (torch.rand(1 << 16, device="cuda") * 2.0 - 1.0).half()
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    flops = [0.0]
+
+    def probe():
+        flops[0] = B.gptq_w4a16_mfma_probe(ops, sink, 4000)
+
+    sec = timed_launches(torch, probe)
+    mfma_only = flops[0] / sec / 1e12
     props = torch.cuda.get_device_properties(0)
     device = {"name": props.name, "arch": getattr(props, "gcnArchName", ""), "compute_units": props.multi_processor_count,
               "memory_GiB": round(props.total_memory / 2**30, 1)}
@@ -348,39 +368,79 @@ def context_lines(torch, reps=10):
     if clock_khz:
         device["max_clock_MHz"] = round(clock_khz / 1e3)
     return {"device": device, "device_copy_GBps_read_plus_write": round(copy_gbs, 1),
-            "torch_matmul_fp16_dense_TFLOPs_M2048_K4096_N22016": round(dense, 1)}
+            "torch_matmul_fp16_dense_TFLOPs_M2048_K4096_N22016": round(dense, 1),
+            "mfma_only_loop_random_operands_TFLOPs": round(mfma_only, 1)}
 
 
-def prefill_leg(torch, B, workloads, layers, M=2048, reps=15, warm=3):
-    """TFLOP/s of the MFMA kernel at M = 2048 on the three Llama-7B weight shapes of layer 0."""
+def timed_launches(torch, fn, min_warm_s=0.06, min_timed_s=0.03):
+    """Mean seconds per call of fn (one kernel launch), after at least min_warm_s of the same launches: the chip's
+    clock governor needs some tens of milliseconds of load before it settles (after an idle gap the first
+    launches run 10-25 % slower), so short bursts measure the ramp, not the kernel."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    fn()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(4):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    est = max(e0.elapsed_time(e1) * 1e-3 / 4, 1e-6)
+    for _ in range(max(4, int(min_warm_s / est))):
+        fn()
+    reps = max(8, int(min_timed_s / est))
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / reps
+
+
+def device_weights(torch, K, N, copies, gen):
+    """Random packed weights drawn on the device (uniform words: every nibble an independent uniform code)."""
+    qws = [torch.randint(-2**31, 2**31 - 1, (K // 8, N), dtype=torch.int32, device="cuda", generator=gen)
+           for _ in range(copies)]
+    qz = torch.randint(-2**31, 2**31 - 1, (K // GROUP, N // 8), dtype=torch.int32, device="cuda", generator=gen)
+    sc = (torch.rand((K // GROUP, N), device="cuda", generator=gen) * 0.009 + 0.001).half()
+    return qws, qz, sc
+
+
+def prefill_leg(torch, B, workloads, layers):
+    """TFLOP/s of the big-tile MFMA kernel: the prefill configuration (M = 512 and 2048 on the three Llama-7B
+    shapes) and the Llama-70B layer set at M = 2048."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4321)
+
+    def run(M, K, N, qw, qz, sc):
+        x = (torch.randn((M, K), device="cuda", generator=gen)).half()
+        out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+        sec = timed_launches(torch, lambda: B.gptq_w4a16_gemm(x, qw, qz, sc, None, out, GROUP))
+        tf = 2.0 * M * K * N / sec / 1e12
+        return {"shape": f"M={M} K={K} N={N}", "us": round(sec * 1e6, 1), "tflops": round(tf, 1),
+                "frac_of_peak": round(tf / MFMA_FP16_PEAK_TFLOPS, 3)}
+
     shapes = workloads.LLAMA_7B
-    results = []
-    for si in (0, 2, 3):  # qkv, gate_up, down
-        sh = shapes[si]
-        t = layers[0][si]
-        x = torch.from_numpy(workloads.make_activations(M, sh.K, seed=workloads.case_seed(3, si))).cuda()
-        out = torch.empty((M, sh.N), dtype=torch.float16, device="cuda")
-        for _ in range(warm):
-            B.gptq_w4a16_gemm(x, t["qweight"], t["qzeros"], t["scales"], None, out, GROUP)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            B.gptq_w4a16_gemm(x, t["qweight"], t["qzeros"], t["scales"], None, out, GROUP)
-        e1.record()
-        torch.cuda.synchronize()
-        sec = e0.elapsed_time(e1) * 1e-3 / reps
-        flops = 2.0 * M * sh.K * sh.N
-        results.append({"shape": f"M={M} K={sh.K} N={sh.N}", "us": round(sec * 1e6, 1),
-                        "tflops": round(flops / sec / 1e12, 1)})
-        del x, out
-    total_flops = sum(2.0 * M * shapes[si].K * shapes[si].N for si in (0, 2, 3))
-    total_s = sum(r["us"] for r in results) * 1e-6
-    agg = total_flops / total_s / 1e12
-    dominant = max(results, key=lambda r: r["us"])
+    rows7 = []
+    for M in (2048, 512):
+        for si in (0, 2, 3):  # qkv, gate_up, down
+            sh, t = shapes[si], layers[0][si]
+            rows7.append(run(M, sh.K, sh.N, t["qweight"], t["qzeros"], t["scales"]))
+    rows70 = []
+    for sh in workloads.LLAMA_70B:
+        qws, qz, sc = device_weights(torch, sh.K, sh.N, 1, gen)
+        rows70.append(run(2048, sh.K, sh.N, qws[0], qz, sc))
+        del qws, qz, sc
+        torch.cuda.empty_cache()
+    head = rows7[:3]
+    total_flops = sum(2.0 * 2048 * shapes[si].K * shapes[si].N for si in (0, 2, 3))
+    agg = total_flops / (sum(r["us"] for r in head) * 1e-6) / 1e12
+    dominant = max(head, key=lambda r: r["us"])
     return {
-        "summary": {"value": round(agg, 1), "unit": "TFLOP/s", "M": M, "shapes": results},
-        "roofline": {"bound": "mfma", "kernel": f"prefill_kernel (fp16 MFMA), {dominant['shape']}",
+        "summary": {"value": round(agg, 1), "unit": "TFLOP/s", "M": 2048, "shapes": head,
+                    "llama7b_M512": rows7[3:], "llama70b_M2048": rows70,
+                    "timing": "per shape: >= 60 ms of untimed launches, then >= 30 ms timed (HIP events)"},
+        "roofline": {"bound": "mfma", "kernel": f"prefill_pipelined_kernel (fp16 MFMA), {dominant['shape']}",
                      "achieved": dominant["tflops"], "peak": MFMA_FP16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(dominant["tflops"] / MFMA_FP16_PEAK_TFLOPS, 4),
                      "traffic": measured_traffic("prefill_m2048_k4096_n22016")},

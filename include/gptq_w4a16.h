@@ -222,6 +222,20 @@ GPTQ_API int gptq_w4a16_unpack(const void *qweight, void *q_out, const void *qze
 GPTQ_API size_t gptq_w4a16_workspace_bytes(int M, int K, int N, int group_size);
 GPTQ_API int gptq_w4a16_set_workspace(void *dev_ptr, size_t bytes);
 
+/*
+ * Measurement aids (no part of the method; bench.py reports them as context for the roofline fractions).
+ * gptq_w4a16_stream_probe: a plain read kernel over buf[0, bytes) (device, 16-byte aligned; bytes rounded down to
+ * 16) with 128-bit loads on 256 workgroups - what any kernel of a GEMV's footprint pays for launch, first-byte
+ * latency and ramp.  sink: at least 256 bytes of device memory that receive a few checksum words.
+ * gptq_w4a16_mfma_probe: `iters` rounds of sixteen independent v_mfma_f32_32x32x16_f16 per wavefront on 512
+ * workgroups, register operands read once from operands[0, bytes) (device fp16 values, caller's choice: the
+ * sustained rate depends on how much the operands toggle); *flops (host, may be NULL) receives the floating
+ * point operations of the launch.  Both only enqueue; errors as everywhere.
+ */
+GPTQ_API int gptq_w4a16_stream_probe(const void *buf, size_t bytes, void *sink, gptq_stream_t stream);
+GPTQ_API int gptq_w4a16_mfma_probe(const void *operands, size_t bytes, void *sink, int iters, double *flops,
+                                   gptq_stream_t stream);
+
 /* Text for a status code (static storage). */
 GPTQ_API const char *gptq_w4a16_strerror(int code);
 

@@ -35,7 +35,8 @@ class Plan(ctypes.Structure):
 
 EXPORTS = ("gptq_w4a16_gemm", "gptq_w4a16_gemm_static", "gptq_w4a16_gemm_plan", "gptq_w4a16_plan_query", "gptq_w4a16_act_order_prepare",
            "gptq_w4a16_gemm_prepared", "gptq_w4a16_shift_zeros", "gptq_w4a16_dequant", "gptq_w4a16_unpack",
-           "gptq_w4a16_workspace_bytes", "gptq_w4a16_set_workspace", "gptq_w4a16_strerror", "gptq_w4a16_version")
+           "gptq_w4a16_workspace_bytes", "gptq_w4a16_set_workspace", "gptq_w4a16_strerror", "gptq_w4a16_version",
+           "gptq_w4a16_stream_probe", "gptq_w4a16_mfma_probe")
 
 
 def load() -> ctypes.CDLL:
@@ -73,6 +74,10 @@ def load() -> ctypes.CDLL:
     lib.gptq_w4a16_set_workspace.restype = ci
     lib.gptq_w4a16_strerror.argtypes = [ci]
     lib.gptq_w4a16_strerror.restype = ctypes.c_char_p
+    lib.gptq_w4a16_stream_probe.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.gptq_w4a16_stream_probe.restype = ci
+    lib.gptq_w4a16_mfma_probe.argtypes = [vp, ctypes.c_size_t, vp, ci, ctypes.POINTER(ctypes.c_double), vp]
+    lib.gptq_w4a16_mfma_probe.restype = ci
     lib.gptq_w4a16_version.argtypes = []
     lib.gptq_w4a16_version.restype = ci
     _lib = lib
@@ -242,3 +247,21 @@ def gptq_w4a16_set_workspace(buf: Optional[torch.Tensor]):
         rc = load().gptq_w4a16_set_workspace(_ptr(buf, torch.uint8, "workspace"), buf.numel())
     if rc != 0:
         raise GptqError(rc, "gptq_w4a16_set_workspace")
+
+
+def gptq_w4a16_stream_probe(buf: torch.Tensor, sink: torch.Tensor):
+    """Plain read of `buf` (any dtype, contiguous): the measurement aid of the header."""
+    rc = load().gptq_w4a16_stream_probe(ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(),
+                                        ctypes.c_void_p(sink.data_ptr()), _stream())
+    if rc != 0:
+        raise GptqError(rc, "gptq_w4a16_stream_probe")
+
+
+def gptq_w4a16_mfma_probe(operands: torch.Tensor, sink: torch.Tensor, iters: int) -> float:
+    """MFMA-only loop on register operands taken from `operands` (fp16); returns the flops of the launch."""
+    flops = ctypes.c_double(0.0)
+    rc = load().gptq_w4a16_mfma_probe(_ptr(operands, torch.float16, "operands"), operands.numel() * 2,
+                                      ctypes.c_void_p(sink.data_ptr()), int(iters), ctypes.byref(flops), _stream())
+    if rc != 0:
+        raise GptqError(rc, "gptq_w4a16_mfma_probe")
+    return float(flops.value)

@@ -38,7 +38,8 @@ def units():
            ("decode.hip", "decode.o", []),
            ("prefill.hip", "prefill.o", []),
            ("skinny.hip", "skinny.o", []),
-           ("act_order.hip", "act_order.o", [])]
+           ("act_order.hip", "act_order.o", []),
+           ("probe.hip", "probe.o", [])]
     for mb in DECODE_BATCHES:
         out.append(("decode_mb.hip", f"decode_mb{mb}.o", [f"-DGPTQ_DECODE_MB={mb}"]))
     for t in PREFILL_TILES:
