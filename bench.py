@@ -30,6 +30,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_FP16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16, published
 GROUP = 128
+QUICK = False
 
 
 def algorithmic_bytes(M, K, N, group=GROUP, act_order=False):
@@ -53,9 +54,14 @@ def main():
     ap.add_argument("--ablation", action="store_true",
                     help="time the vector kernel with each of the paper's three techniques taken out (part of the "
                          "default run; this switch keeps it when --no-sweep drops the other side tables)")
+    ap.add_argument("--quick", action="store_true",
+                    help="few launches per leg and no clock settling: for runs under a profiler, where the launch "
+                         "counts matter and the printed rates do not")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference kernel for the HBM traffic counters)")
     args = ap.parse_args()
+    global QUICK
+    QUICK = args.quick
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -385,6 +391,8 @@ def timed_launches(torch, fn, min_warm_s=0.06, min_timed_s=0.03):
     e1.record()
     torch.cuda.synchronize()
     est = max(e0.elapsed_time(e1) * 1e-3 / 4, 1e-6)
+    if QUICK:
+        return est
     for _ in range(max(4, int(min_warm_s / est))):
         fn()
     reps = max(8, int(min_timed_s / est))

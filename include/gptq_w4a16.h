@@ -110,7 +110,7 @@ GPTQ_API int gptq_w4a16_gemm_static(const void *x, const void *qweight, const vo
 
 typedef struct gptq_w4a16_plan {
     int kernel;      /* 0 auto, 1 vector split-K kernel (any M, processed 16 rows at a time), 2 big-tile MFMA kernel,
-                        3 small-batch MFMA kernel (M <= 64, processed 32 rows at a time; no g_idx,
+                        3 small-batch MFMA kernel (M <= 128, processed 64 rows at a time; no g_idx,
                         group_size % 128 == 0; else falls back) */
     int split_k;     /* number of K slices (all three kernels; the big-tile kernel splits by itself only on
                         its 128x128 and 64x128 tiles); 0 auto */

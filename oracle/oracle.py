@@ -17,6 +17,9 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gptq_oracle.c")
 _LIB = os.path.join(_HERE, "libgptq_oracle.so")
+# The mutation test of the pins (tests/test_oracle_mutants.py) points this at a library built from a patched copy
+# of the C file; nothing else sets it.
+_OVERRIDE = os.environ.get("GPTQ_ORACLE_LIB_OVERRIDE")
 _lib = None
 
 
@@ -32,8 +35,11 @@ def build(force: bool = True) -> str:
 def _load():
     global _lib
     if _lib is None:
-        build(force=False)
-        _lib = ctypes.CDLL(_LIB)
+        if _OVERRIDE:
+            _lib = ctypes.CDLL(_OVERRIDE)
+        else:
+            build(force=False)
+            _lib = ctypes.CDLL(_LIB)
         _lib.oracle_num_threads.restype = ctypes.c_int
     return _lib
 

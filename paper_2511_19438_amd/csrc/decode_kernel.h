@@ -21,6 +21,7 @@
 // wavefront load touches 4 rows x 256 contiguous bytes.
 #pragma once
 
+#include "exchange.h"
 #include "kernels.h"
 
 namespace gptq {
@@ -516,16 +517,13 @@ __global__ __launch_bounds__((ABL & kEightWaves) ? 512 : 256) void decode_kernel
                         __hip_atomic_fetch_add(a.partial + (size_t)m * N + n0 + c, acc[m][c], __ATOMIC_RELAXED,
                                                __HIP_MEMORY_SCOPE_AGENT);
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (tid == 0) {
-            const unsigned prev =
-                __hip_atomic_fetch_add(a.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_last = (prev == (unsigned)(a.split_k - 1));
-        }
+        if (tid == 0)
+            s_last = (slice_arrive(a.counters + tile) == (unsigned)(a.split_k - 1));
         __syncthreads();
         if (s_last) {
+            slice_acquire();
             for (int i = tid; i < a.M * CT; i += kThreads) {
                 const int m = i / CT;
                 const int n = tile * CT + (i - m * CT);
@@ -581,17 +579,14 @@ __global__ __launch_bounds__((ABL & kEightWaves) ? 512 : 256) void decode_kernel
 
     // ---- combine the K slices: the last workgroup of this column tile adds them in slice order ----
     if (a.split_k > 1) {
-        // all partial stores of this workgroup have been acknowledged before its arrival is counted
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        // all partial stores of this workgroup have been acknowledged before its arrival is counted (exchange.h)
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (tid == 0) {
-            const unsigned prev =
-                __hip_atomic_fetch_add(a.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_last = (prev == (unsigned)(a.split_k - 1));
-        }
+        if (tid == 0)
+            s_last = (slice_arrive(a.counters + tile) == (unsigned)(a.split_k - 1));
         __syncthreads();
         if (s_last) {
+            slice_acquire();
             for (int i = tid; i < a.M * CT; i += kThreads) {
                 const int m = i / CT;
                 const int n = tile * CT + (i - m * CT);

@@ -60,8 +60,8 @@ bool decode_plan_fits(const Problem &p, const DecodePlan &plan);
 // Whether the ablation variants of the vector kernel (DecodePlan::flags != 0) exist for this problem.
 bool decode_ablation_supported(const Problem &p);
 
-// ---- small batch: MFMA kernel with the vector kernel's split-K decomposition, M <= 64 ----
-constexpr int kSkinnyMaxM = 64;
+// ---- small batch: MFMA kernel with the vector kernel's split-K decomposition, M <= 128 (64 rows per launch) ----
+constexpr int kSkinnyMaxM = 128;
 struct SkinnyPlan {
     int cols_per_wg;      // 64 (wavefronts split the K slice) or 256 (wavefronts side by side); 0 = choose
     int split_k;          // number of K slices (0 = choose)

@@ -38,6 +38,7 @@
 
 #include <type_traits>
 
+#include "exchange.h"
 #include "kernels.h"
 
 namespace gptq {
@@ -184,7 +185,7 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[TM][TN], half_
 // last workgroup of the tile to arrive adds them in slice order (deterministic), then goes on to store the
 // tile.  The values travel in pairs - 64-bit accesses, pair p of thread t at [p][t]: coalesced - and the last
 // arriver loads several slices before it uses any, so the combine costs a few scratch round trips instead of
-// one per slice.  Device-scope accesses and an arrival counter, no device-wide fence (see the vector kernel).
+// one per slice.  Device-scope accesses and an arrival counter with release / acquire at agent scope (exchange.h).
 // Returns false in the workgroups that are not the last of their tile.  Partial layout:
 // [split_k][tiles][ACC / 2 pairs][256 threads] x 8 bytes.
 template <int ACC>
@@ -206,17 +207,14 @@ __device__ __forceinline__ bool combine_slices(float (&v)[ACC], const Args &a, i
         __hip_atomic_store(mine + (size_t)p * kThreads, __builtin_bit_cast(unsigned long long, pair), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0);  // every partial store of this workgroup has been acknowledged
+    __builtin_amdgcn_s_waitcnt(0);  // every partial store of this workgroup has been acknowledged (exchange.h)
     __syncthreads();
-    if (tid == 0) {
-        const unsigned prev =
-            __hip_atomic_fetch_add(a.counters + tile_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = (prev == (unsigned)(a.split_k - 1));
-    }
+    if (tid == 0)
+        s_last = (slice_arrive(a.counters + tile_id) == (unsigned)(a.split_k - 1));
     __syncthreads();
     if (!s_last)
         return false;
+    slice_acquire();
 #pragma unroll
     for (int e = 0; e < ACC; ++e)
         v[e] = 0.f;

@@ -14,13 +14,13 @@ int ceil_div(int a, int b)
     return (a + b - 1) / b;
 }
 
-// Batches of more than 32 rows are processed 32 rows at a time (one launch each, same stream): the weights
+// Batches of more than 64 rows are processed 64 rows at a time (one launch each, same stream): the weights
 // are streamed once per launch, the second time mostly from the memory-side cache.
-constexpr int kRowsPerLaunch = 32;
+constexpr int kRowsPerLaunch = 64;
 
 int row_blocks(int M)
 {
-    return M <= 16 ? 1 : 2;
+    return M <= 16 ? 1 : M <= 32 ? 2 : 4;
 }
 
 int rows_of_launch(int M)
@@ -28,10 +28,11 @@ int rows_of_launch(int M)
     return M < kRowsPerLaunch ? M : kRowsPerLaunch;
 }
 
-// Wavefronts per workgroup: eight where the 64-column workgroups have a compute unit each, else four.
-int waves_of(int tiles_n, int split_k, int wn)
+// Wavefronts per workgroup: eight where the 64-column workgroups have a compute unit each, else four.  Four row
+// blocks need more registers than two wavefronts per SIMD leave each: always four.
+int waves_of(int tiles_n, int split_k, int wn, int tm)
 {
-    return (wn == 1 && (long long)tiles_n * split_k <= 256) ? 8 : 4;
+    return (wn == 1 && tm <= 2 && (long long)tiles_n * split_k <= 256) ? 8 : 4;
 }
 
 template <int TM, int WN, int WAVES>
@@ -92,7 +93,7 @@ void skinny_make_plan(const Problem &p, SkinnyPlan &plan)
         if (split < 1)
             split = 1;
         // narrow tiles: one unit per wavefront and turn
-        const int quantum = plan.cols_per_wg == 64 ? waves_of(tiles_n, split, 1) : 1;
+        const int quantum = plan.cols_per_wg == 64 ? waves_of(tiles_n, split, 1, row_blocks(launch_m)) : 1;
         ups = ceil_div(ceil_div(total_units, split), quantum) * quantum;
         if (ups > total_units)
             ups = total_units;
@@ -144,16 +145,18 @@ hipError_t launch_skinny(const Problem &p, const SkinnyPlan &plan, void *workspa
         // 64-column workgroups read the activations straight from global memory
         const bool direct = wn == 1;
         const size_t xs = direct ? 0 : (size_t)rows * plan.units_per_slice * skinny::kUnitK * sizeof(half_t);
-        const int waves = waves_of(a.tiles_n, a.split_k, wn);
+        const int waves = waves_of(a.tiles_n, a.split_k, wn, tm);
         const size_t red = (size_t)waves * rows * skinny::kCols * sizeof(float);  // [waves/wn][rows][64*wn]
         const size_t lds = xs > red ? xs : red;
         hipError_t err;
         if (wn == 4)
-            err = tm == 1 ? launch_tm<1, 4, 4>(a, lds, stream) : launch_tm<2, 4, 4>(a, lds, stream);
+            err = tm == 1 ? launch_tm<1, 4, 4>(a, lds, stream)
+                          : tm == 2 ? launch_tm<2, 4, 4>(a, lds, stream) : launch_tm<4, 4, 4>(a, lds, stream);
         else if (waves == 8)
             err = tm == 1 ? launch_tm<1, 1, 8>(a, lds, stream) : launch_tm<2, 1, 8>(a, lds, stream);
         else
-            err = tm == 1 ? launch_tm<1, 1, 4>(a, lds, stream) : launch_tm<2, 1, 4>(a, lds, stream);
+            err = tm == 1 ? launch_tm<1, 1, 4>(a, lds, stream)
+                          : tm == 2 ? launch_tm<2, 1, 4>(a, lds, stream) : launch_tm<4, 1, 4>(a, lds, stream);
         if (err != hipSuccess)
             return err;
     }

@@ -1,4 +1,4 @@
-// Small-batch MFMA kernel for the W4A16 GPTQ matrix multiply (5 <= M <= 128), gfx950.
+// Small-batch MFMA kernel for the W4A16 GPTQ matrix multiply (2 <= M <= 64 per launch), gfx950.
 //
 // Between the vector kernel (which runs out of vector ALU throughput once every weight has to be
 // multiplied with more than a few batch rows) and the big-tile MFMA kernel (which needs hundreds of rows
@@ -19,6 +19,7 @@
 // other kernels.
 #pragma once
 
+#include "exchange.h"
 #include "kernels.h"
 
 #include <type_traits>
@@ -219,9 +220,13 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
     // fp32:  acc += s * sum_k x_k (q_k - z).  (Contracting the biased codes and cancelling sum_k x_k * bias
     // afterwards saves the adds but loses digits to the size of that sum: activations with a common offset of a
     // few tens then leave the tolerance band.)
+    // From four row blocks on (SCALE_B) the scale goes into the B operand instead (one more packed multiply per
+    // pair: the fp16 weight itself, rounded once) and the MFMAs add straight into the running sums: scaling the
+    // sums of 4 x 16 rows per group would cost as many operations and twice the accumulator registers.
+    constexpr bool SCALE_B = TM >= 4;
     auto consume = [&](int u, const Regs &r) {
         const int j = u - u0;
-        half2_t neg_lo[4], neg_hi[4];
+        half2_t neg_lo[4], neg_hi[4], s2[4];
         float sf[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -232,8 +237,9 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
             const uint32_t pair = t < 2 ? r.sc.x : r.sc.y;
             const uint16_t sb = (uint16_t)((t & 1) ? (pair >> 16) : (pair & 0xffffu));
             sf[t] = (float)__builtin_bit_cast(half_t, sb);
+            s2[t] = as_half2((uint32_t)sb | ((uint32_t)sb << 16));
         }
-        float4_t d[TM][4];
+        float4_t d[SCALE_B ? 1 : TM][4];
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
             const uint32_t w[4] = {r.w[st].x, r.w[st].y, r.w[st].z, r.w[st].w};
@@ -242,10 +248,16 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
             for (int t = 0; t < 4; ++t) {
                 const uint32_t w8 = w[t] >> 8;
                 // k order inside the operand: (0,4) (1,5) (2,6) (3,7)
-                const half2_t c0 = as_half2((w[t] & magic.mask_lo) | magic.bias_lo) + neg_lo[t];
-                const half2_t c1 = as_half2((w[t] & magic.mask_hi) | magic.bias_hi) + neg_hi[t];
-                const half2_t c2 = as_half2((w8 & magic.mask_lo) | magic.bias_lo) + neg_lo[t];
-                const half2_t c3 = as_half2((w8 & magic.mask_hi) | magic.bias_hi) + neg_hi[t];
+                half2_t c0 = as_half2((w[t] & magic.mask_lo) | magic.bias_lo) + neg_lo[t];
+                half2_t c1 = as_half2((w[t] & magic.mask_hi) | magic.bias_hi) + neg_hi[t];
+                half2_t c2 = as_half2((w8 & magic.mask_lo) | magic.bias_lo) + neg_lo[t];
+                half2_t c3 = as_half2((w8 & magic.mask_hi) | magic.bias_hi) + neg_hi[t];
+                if (SCALE_B) {
+                    c0 *= s2[t];
+                    c1 *= s2[t];
+                    c2 *= s2[t];
+                    c3 *= s2[t];
+                }
                 b[t] = half8_t{c0[0], c0[1], c1[0], c1[1], c2[0], c2[1], c3[0], c3[1]};
             }
             const int c = (j * 4 + st) * 4 + kg;  // 16-byte chunk of the activation row
@@ -267,17 +279,23 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
                 const half8_t av = __builtin_bit_cast(half8_t, xp);
                 const float4_t zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    d[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b[t], st == 0 ? zero : d[i][t], 0, 0, 0);
+                for (int t = 0; t < 4; ++t) {
+                    if (SCALE_B)
+                        acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b[t], acc[i][t], 0, 0, 0);
+                    else
+                        d[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b[t], st == 0 ? zero : d[i][t], 0, 0, 0);
+                }
             }
         }
+        if (!SCALE_B) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+                for (int t = 0; t < 4; ++t)
 #pragma unroll
-                for (int rr = 0; rr < 4; ++rr)
-                    acc[i][t][rr] = __builtin_fmaf(sf[t], d[i][t][rr], acc[i][t][rr]);
+                    for (int rr = 0; rr < 4; ++rr)
+                        acc[i][t][rr] = __builtin_fmaf(sf[t], d[i][t][rr], acc[i][t][rr]);
+        }
     };
 
     if (active) {
@@ -286,9 +304,15 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
         // boundary the accumulators are pinned (empty asm) and the scheduler stopped, so that the loads of
         // the unit after next are issued after this unit's arithmetic: two units in flight, not three.
         auto unit_boundary = [&]() {
+            // (with four row blocks the running sums live in accumulation registers: pinning them as vector
+            // registers would copy all 64 out and back at every unit)
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                asm volatile("" : "+v"(acc[i][0]), "+v"(acc[i][1]), "+v"(acc[i][2]), "+v"(acc[i][3])::"memory");
+            for (int i = 0; i < TM; ++i) {
+                if (TM >= 4)
+                    asm volatile("" : "+a"(acc[i][0]), "+a"(acc[i][1]), "+a"(acc[i][2]), "+a"(acc[i][3])::"memory");
+                else
+                    asm volatile("" : "+v"(acc[i][0]), "+v"(acc[i][1]), "+v"(acc[i][2]), "+v"(acc[i][3])::"memory");
+            }
             __builtin_amdgcn_sched_barrier(0);
         };
         int u = wu0;
@@ -343,16 +367,13 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
 
     // ---- combine the K slices: the last workgroup of this column tile adds them in slice order ----
     if (a.split_k > 1) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_s_waitcnt(0);  // every partial store of this workgroup has been acknowledged
+        __builtin_amdgcn_s_waitcnt(0);  // every partial store of this workgroup has been acknowledged (exchange.h)
         __syncthreads();
-        if (tid == 0) {
-            const unsigned prev =
-                __hip_atomic_fetch_add(a.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_last = (prev == (unsigned)(a.split_k - 1));
-        }
+        if (tid == 0)
+            s_last = (slice_arrive(a.counters + tile) == (unsigned)(a.split_k - 1));
         __syncthreads();
         if (s_last) {
+            slice_acquire();
             // All partial sums a thread needs are requested before the first is used (up to four outputs
             // times eight slices in flight), so the combine costs one scratch round trip, not one per
             // output; the additions stay in slice order.

@@ -91,6 +91,31 @@ def test_config2_act_order(B, M):
     check_sampled(B, M, sh.K, sh.N, workloads.case_seed(2), act_order=True)
 
 
+@pytest.mark.parametrize("M", [1, 8, 16, 40])
+def test_config2_act_order_through_the_one_time_repack(B, M):
+    """The act-order configuration at full size through gptq_w4a16_act_order_prepare + gptq_w4a16_gemm_prepared,
+    against the ORACLE's act-order result (raw qweight and g_idx)."""
+    sh = workloads.ACT_ORDER_SHAPE
+    seed = workloads.case_seed(2)
+    w, d = device_weights(sh.K, sh.N, seed, act_order=True)
+    qs = torch.empty_like(d["qweight"])
+    perm = torch.empty(sh.K, dtype=torch.int32, device="cuda")
+    B.gptq_w4a16_act_order_prepare(d["qweight"], d["g_idx"], qs, perm, GROUP)
+    order = np.argsort(w["g_idx"], kind="stable").astype(np.int32)
+    assert np.array_equal(perm.cpu().numpy(), order)
+    x = workloads.make_activations(M, sh.K, seed=seed + M)
+    out = torch.full((M, sh.N), float("nan"), dtype=torch.float16, device="cuda")
+    B.gptq_w4a16_gemm_prepared(torch.from_numpy(x).cuda(), qs, d["qzeros"], d["scales"], perm, out, GROUP)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    m_idx, n_idx = workloads.sample_positions(M, sh.N, SAMPLES, seed=seed + 11)
+    m_idx[:4] = [0, 0, M - 1, M - 1]
+    n_idx[:4] = [0, sh.N - 1, 0, sh.N - 1]
+    ref = oracle.gemm_ref_sampled(x, w["qweight"], w["qzeros"], w["scales"], w["g_idx"], GROUP, m_idx, n_idx)
+    ratio = np.abs(got[m_idx, n_idx].astype(np.float64) - ref) / (TOL * np.maximum(1.0, np.abs(ref)))
+    assert float(ratio.max()) <= 0.25, f"repacked act-order M={M}: err/tol = {ratio.max():.3f}"
+
+
 @pytest.mark.parametrize("shape_index", [0, 2, 3])
 @pytest.mark.parametrize("M", workloads.PREFILL_BATCHES)
 def test_config3_prefill_llama7b(B, shape_index, M):

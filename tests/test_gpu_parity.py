@@ -259,7 +259,7 @@ SKINNY_SHAPES = [
 
 
 @pytest.mark.parametrize("tile", [64, 256])
-@pytest.mark.parametrize("M", [1, 5, 8, 16, 17, 32, 33, 64])
+@pytest.mark.parametrize("M", [1, 5, 8, 16, 17, 32, 33, 49, 64, 65, 100, 128])
 @pytest.mark.parametrize("K,N,group", SKINNY_SHAPES)
 def test_small_batch_mfma_kernel_matches_oracle(B, M, K, N, group, tile):
     case = workloads.make_case(M, K, N, group, seed=3 * K + N + M)
@@ -270,7 +270,7 @@ def test_small_batch_mfma_kernel_matches_oracle(B, M, K, N, group, tile):
 
 @pytest.mark.parametrize("tile", [64, 256])
 @pytest.mark.parametrize("split_k", [1, 2, 3, 5, 16])
-@pytest.mark.parametrize("M", [8, 40])
+@pytest.mark.parametrize("M", [8, 40, 64, 90])
 def test_small_batch_mfma_kernel_splits(B, split_k, M, tile):
     K, N, group = 2048, 776, 128
     case = workloads.make_case(M, K, N, group, seed=177 + M)
@@ -281,7 +281,7 @@ def test_small_batch_mfma_kernel_splits(B, split_k, M, tile):
 
 def test_small_batch_request_falls_back_when_unsupported(B):
     # act-order and group sizes that are not multiples of 128 are served by the other kernels
-    for M, K, N, group, act in [(8, 512, 136, 64, False), (8, 512, 136, 128, True), (100, 512, 136, 128, False)]:
+    for M, K, N, group, act in [(8, 512, 136, 64, False), (8, 512, 136, 128, True), (200, 512, 136, 128, False)]:
         case = workloads.make_case(M, K, N, group, seed=M + N, act_order=act)
         ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], case["g_idx"], group)
         out = run_gemm(B, case, group, B.Plan(kernel=3))
@@ -290,7 +290,7 @@ def test_small_batch_request_falls_back_when_unsupported(B):
 
 # ------------------------------------------------------------------ exactness pins in the GEMM kernels themselves
 
-@pytest.mark.parametrize("M,plan_kernel", [(1, 1), (4, 1), (8, 1), (16, 1), (40, 2), (300, 2), (8, 3), (40, 3)])
+@pytest.mark.parametrize("M,plan_kernel", [(1, 1), (4, 1), (8, 1), (16, 1), (40, 2), (300, 2), (8, 3), (24, 3), (40, 3), (64, 3)])
 @pytest.mark.parametrize("act", [False, True])
 def test_one_hot_rows_return_weight_rows_bit_exact(B, M, plan_kernel, act):
     K, N, group = 1024, 264, 128
