@@ -28,10 +28,10 @@ int rows_of_launch(int M)
     return M < kRowsPerLaunch ? M : kRowsPerLaunch;
 }
 
-// Wavefronts per workgroup: eight where the 64-column workgroups have a compute unit each, else four.  Four row
-// blocks need more registers than two wavefronts per SIMD leave each: always four.
+// Wavefronts per workgroup: eight where the 64-column workgroups have a compute unit each, else four.
 int waves_of(int tiles_n, int split_k, int wn, int tm)
 {
+    // (four row blocks do not fit the 256 registers that two wavefronts per SIMD leave each)
     return (wn == 1 && tm <= 2 && (long long)tiles_n * split_k <= 256) ? 8 : 4;
 }
 
@@ -88,6 +88,18 @@ void skinny_make_plan(const Problem &p, SkinnyPlan &plan)
         if (max_split < 1)
             max_split = 1;
         int split = (256 + tiles_n / 2) / tiles_n;
+        // A few workgroups more than compute units is the worst case (four-wavefront workgroups, some units with
+        // two of them): 160 tiles x 2 slices on 8192x10240 measured 15.2 us at M = 2 against 13.4 unsplit.
+        if (tiles_n > 128)
+            split = 1;
+        if (plan.cols_per_wg == 256) {
+            // wide tiles (very wide layers): eight slices, within a quarter of the weight bytes for the partial
+            // sums (8192x57344 at M = 2: 46.1 us with eight slices, 49.9 with four)
+            split = 8;
+            max_split = p.K / (64 * launch_m);
+            if (max_split < 1)
+                max_split = 1;
+        }
         if (split > max_split)
             split = max_split;
         if (split < 1)

@@ -111,7 +111,12 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
     // from global memory (L2), in the same pipeline as the weights.  With 256-column workgroups the four
     // wavefronts share the slice and the activations are staged once in LDS.
     constexpr bool DIRECT = WN == 1;
-    using Regs = UnitRegs<DIRECT ? TM : 0>;
+    // DIRECT with four row blocks: the A operands of two units in flight would take 128 registers.  They are kept
+    // for ONE unit instead and refilled step by step: as soon as a 32-k step's operands have been permuted into
+    // the MFMA's k order, the same registers receive that step of the NEXT unit (from L2: a four-step lead is
+    // enough), which leaves room for two wavefronts per SIMD.
+    constexpr bool XSTEP = DIRECT && TM >= 4;
+    using Regs = UnitRegs<(DIRECT && !XSTEP) ? TM : 0>;
 
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int s_last;
@@ -164,7 +169,7 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
         r.sc = *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(a.scales + (size_t)grp * N) + voff_s);
         r.zb = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(a.qzeros + (size_t)grp * (N >> 3)) +
                                                    voff_z);
-        if (DIRECT) {
+        if (DIRECT && !XSTEP) {
             const half_t *xrow = a.x + (size_t)uc * kUnitK;
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -174,11 +179,24 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
                                                                      voff_x[i]);
         }
     };
+    u32x4_t xstep[XSTEP ? TM : 1][4];  // XSTEP: the A operands of the unit being consumed, refilled per step
+    auto issue_x = [&](int u, int st) {
+        const half_t *xrow = a.x + (size_t)min(u, u1 - 1) * kUnitK + st * 32;
+#pragma unroll
+        for (int i = 0; i < (XSTEP ? TM : 1); ++i)
+            xstep[i][st] = *reinterpret_cast<const u32x4_t *>(reinterpret_cast<const char *>(xrow) + voff_x[i]);
+    };
 
     Regs ra, rb;
     const bool active = wu0 < wu1;
-    if (active)
+    if (active) {
         issue(wu0, ra);  // in flight while the activations are staged (when they are)
+        if (XSTEP) {
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+                issue_x(wu0, st);
+        }
+    }
 
     // ---- stage the activations global -> LDS by DMA (no registers, all loads in flight at once): 16-byte slot p
     //      of the buffer holds, for row m = p / chunks, the chunk whose index is p % chunks with its low four
@@ -224,7 +242,8 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
     // pair: the fp16 weight itself, rounded once) and the MFMAs add straight into the running sums: scaling the
     // sums of 4 x 16 rows per group would cost as many operations and twice the accumulator registers.
     constexpr bool SCALE_B = TM >= 4;
-    auto consume = [&](int u, const Regs &r) {
+    auto consume = [&](int u, const Regs &r, auto refill) {
+        constexpr bool REFILL = decltype(refill)::value;  // XSTEP: fetch the next unit's A operands step by step
         const int j = u - u0;
         half2_t neg_lo[4], neg_hi[4], s2[4];
         float sf[4];
@@ -243,7 +262,29 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
             const uint32_t w[4] = {r.w[st].x, r.w[st].y, r.w[st].z, r.w[st].w};
-            half8_t b[4];
+            const int c = (j * 4 + st) * 4 + kg;  // 16-byte chunk of the activation row
+            half8_t av[TM];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                u32x4_t xv;
+                if (XSTEP) {
+                    xv = xstep[i][st];
+                } else if (DIRECT) {
+                    xv = r.xa[i][st];
+                } else {
+                    const int m = 16 * i + cq;  // the A operand lane holds row lane % 16
+                    const int pc = (c & ~15) | ((c ^ m) & 15);
+                    xv = *reinterpret_cast<const u32x4_t *>(xs + (size_t)m * Ls + pc * 8);
+                }
+                // the same k order for the activations: halves (0,4) (1,5) (2,6) (3,7)
+                const u32x4_t xp = {__builtin_amdgcn_perm(xv[2], xv[0], 0x05040100u),
+                                    __builtin_amdgcn_perm(xv[2], xv[0], 0x07060302u),
+                                    __builtin_amdgcn_perm(xv[3], xv[1], 0x05040100u),
+                                    __builtin_amdgcn_perm(xv[3], xv[1], 0x07060302u)};
+                av[i] = __builtin_bit_cast(half8_t, xp);
+            }
+            if (XSTEP && REFILL)
+                issue_x(u + 1, st);
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const uint32_t w8 = w[t] >> 8;
@@ -258,32 +299,14 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
                     c2 *= s2[t];
                     c3 *= s2[t];
                 }
-                b[t] = half8_t{c0[0], c0[1], c1[0], c1[1], c2[0], c2[1], c3[0], c3[1]};
-            }
-            const int c = (j * 4 + st) * 4 + kg;  // 16-byte chunk of the activation row
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                u32x4_t xv;
-                if (DIRECT) {
-                    xv = r.xa[i][st];
-                } else {
-                    const int m = 16 * i + cq;  // the A operand lane holds row lane % 16
-                    const int pc = (c & ~15) | ((c ^ m) & 15);
-                    xv = *reinterpret_cast<const u32x4_t *>(xs + (size_t)m * Ls + pc * 8);
-                }
-                // the same k order for the activations: halves (0,4) (1,5) (2,6) (3,7)
-                const u32x4_t xp = {__builtin_amdgcn_perm(xv[2], xv[0], 0x05040100u),
-                                    __builtin_amdgcn_perm(xv[2], xv[0], 0x07060302u),
-                                    __builtin_amdgcn_perm(xv[3], xv[1], 0x05040100u),
-                                    __builtin_amdgcn_perm(xv[3], xv[1], 0x07060302u)};
-                const half8_t av = __builtin_bit_cast(half8_t, xp);
+                const half8_t b = half8_t{c0[0], c0[1], c1[0], c1[1], c2[0], c2[1], c3[0], c3[1]};
                 const float4_t zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
+                for (int i = 0; i < TM; ++i) {
                     if (SCALE_B)
-                        acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b[t], acc[i][t], 0, 0, 0);
+                        acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av[i], b, acc[i][t], 0, 0, 0);
                     else
-                        d[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b[t], st == 0 ? zero : d[i][t], 0, 0, 0);
+                        d[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av[i], b, st == 0 ? zero : d[i][t], 0, 0, 0);
                 }
             }
         }
@@ -315,23 +338,25 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
             }
             __builtin_amdgcn_sched_barrier(0);
         };
+        const std::integral_constant<bool, true> more;
+        const std::integral_constant<bool, false> last;
         int u = wu0;
         while (u + 2 < wu1) {
             issue(u + 1, rb);
-            consume(u, ra);
+            consume(u, ra, more);
             unit_boundary();
             issue(u + 2, ra);
-            consume(u + 1, rb);
+            consume(u + 1, rb, more);
             unit_boundary();
             u += 2;
         }
         if (u + 2 == wu1) {
             issue(u + 1, rb);
-            consume(u, ra);
+            consume(u, ra, more);
             unit_boundary();
-            consume(u + 1, rb);
+            consume(u + 1, rb, last);
         } else {
-            consume(u, ra);
+            consume(u, ra, last);
         }
     }
 
