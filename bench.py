@@ -296,6 +296,29 @@ def sweep_tables(torch, B, workloads, layers):
                                  "plain_format_same_shape": [round(c, 2), round(nbytes / c / 1e3)]})
     del qws, sorted_qws
     torch.cuda.empty_cache()
+    # format variants: smaller quantisation groups on the qkv shape (M = 1: vector kernel; M = 8: small-batch kernel
+    # with two / four groups per 128-k unit; M = 2048: big-tile kernel, pipelined for multiples of 64)
+    sh = shapes[0]
+    out["group_sizes"] = []
+    for group in (128, 64, 32):
+        copies = 24
+        qws = [torch.randint(-2**31, 2**31 - 1, (sh.K // 8, sh.N), dtype=torch.int32, device="cuda", generator=gen)
+               for _ in range(copies)]
+        qz = torch.randint(-2**31, 2**31 - 1, (sh.K // group, sh.N // 8), dtype=torch.int32, device="cuda", generator=gen)
+        sc = (torch.rand((sh.K // group, sh.N), device="cuda", generator=gen) * 0.009 + 0.001).half()
+        row = {"shape": f"{sh.name} K={sh.K} N={sh.N} group={group}"}
+        for M in (1, 8):
+            x = torch.randn((M, sh.K), device="cuda").half()
+            o = torch.empty((M, sh.N), dtype=torch.float16, device="cuda")
+            us = graph_us(torch, [(lambda q=q: B.gptq_w4a16_gemm(x, q, qz, sc, None, o, group)) for q in qws])
+            row[f"M={M}"] = [round(us, 2), round(algorithmic_bytes(M, sh.K, sh.N, group) / us / 1e3)]
+        x = torch.randn((2048, sh.K), device="cuda").half()
+        o = torch.empty((2048, sh.N), dtype=torch.float16, device="cuda")
+        sec = timed_launches(torch, lambda: B.gptq_w4a16_gemm(x, qws[0], qz, sc, None, o, group))
+        row["M=2048"] = [round(sec * 1e6, 1), f"{2.0 * 2048 * sh.K * sh.N / sec / 1e12:.0f} TFLOP/s"]
+        out["group_sizes"].append(row)
+        del qws, qz, sc, x, o
+        torch.cuda.empty_cache()
     for sh in workloads.LLAMA_70B:
         copies = max(2, int(1.3e9 // (sh.K * sh.N // 2)) + 1)
         qws, qz, sc = device_weights(torch, sh.K, sh.N, copies, gen)

@@ -35,10 +35,10 @@ int waves_of(int tiles_n, int split_k, int wn, int tm)
     return (wn == 1 && tm <= 2 && (long long)tiles_n * split_k <= 256) ? 8 : 4;
 }
 
-template <int TM, int WN, int WAVES>
+template <int TM, int WN, int WAVES, int GPU = 1>
 hipError_t launch_tm(const skinny::Args &a, size_t lds, hipStream_t stream)
 {
-    auto kernel = skinny::skinny_kernel<TM, WN, WAVES>;
+    auto kernel = skinny::skinny_kernel<TM, WN, WAVES, GPU>;
     if (lds > 48 * 1024) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -53,8 +53,13 @@ hipError_t launch_tm(const skinny::Args &a, size_t lds, hipStream_t stream)
 
 bool skinny_supported(const Problem &p)
 {
-    return p.g_idx == nullptr && p.M >= 1 && p.M <= kSkinnyMaxM && p.group_size % 128 == 0 && p.N >= 8 &&
-           ceil_div(p.N, skinny::kCols) <= kMaxColumnTiles;
+    if (p.g_idx != nullptr || p.M < 1 || p.M > kSkinnyMaxM || p.N < 8 || p.K % skinny::kUnitK != 0 ||
+        ceil_div(p.N, skinny::kCols) > kMaxColumnTiles)
+        return false;
+    // groups of 64 and 32 k: the 64-column kernel with up to two row blocks
+    if (p.group_size == 64 || p.group_size == 32)
+        return p.M <= 32;
+    return p.group_size % 128 == 0;
 }
 
 void skinny_make_plan(const Problem &p, SkinnyPlan &plan)
@@ -62,6 +67,8 @@ void skinny_make_plan(const Problem &p, SkinnyPlan &plan)
     const int launch_m = rows_of_launch(p.M);
     const int rows = 16 * row_blocks(launch_m);
     const int total_units = p.K / skinny::kUnitK;
+    if (p.group_size < skinny::kUnitK)
+        plan.cols_per_wg = 64;  // the small-group variants exist for the 64-column workgroup
     if (plan.cols_per_wg != 64 && plan.cols_per_wg != 256) {
         // Wide tiles stage the activations once for four times as many weights, but a workgroup's wavefronts
         // then walk the whole slice: that only pays (measured) once the columns alone spread over most of
@@ -142,7 +149,7 @@ hipError_t launch_skinny(const Problem &p, const SkinnyPlan &plan, void *workspa
         a.M = (p.M - m0) < kRowsPerLaunch ? (p.M - m0) : kRowsPerLaunch;
         a.K = p.K;
         a.N = p.N;
-        a.units_per_group = p.group_size / skinny::kUnitK;
+        a.units_per_group = p.group_size >= skinny::kUnitK ? p.group_size / skinny::kUnitK : 1;
         a.unit_group_shift = -1;
         for (int sh = 0; sh < 20; ++sh)
             if ((1 << sh) == a.units_per_group)
@@ -161,7 +168,17 @@ hipError_t launch_skinny(const Problem &p, const SkinnyPlan &plan, void *workspa
         const size_t red = (size_t)waves * rows * skinny::kCols * sizeof(float);  // [waves/wn][rows][64*wn]
         const size_t lds = xs > red ? xs : red;
         hipError_t err;
-        if (wn == 4)
+        const int gpu = p.group_size >= skinny::kUnitK ? 1 : skinny::kUnitK / p.group_size;
+        if (gpu > 1) {
+            if (wn != 1 || tm > 2)
+                return hipErrorInvalidValue;  // refused by skinny_supported / skinny_make_plan
+            if (gpu == 2)
+                err = waves == 8 ? (tm == 1 ? launch_tm<1, 1, 8, 2>(a, lds, stream) : launch_tm<2, 1, 8, 2>(a, lds, stream))
+                                 : (tm == 1 ? launch_tm<1, 1, 4, 2>(a, lds, stream) : launch_tm<2, 1, 4, 2>(a, lds, stream));
+            else
+                err = waves == 8 ? (tm == 1 ? launch_tm<1, 1, 8, 4>(a, lds, stream) : launch_tm<2, 1, 8, 4>(a, lds, stream))
+                                 : (tm == 1 ? launch_tm<1, 1, 4, 4>(a, lds, stream) : launch_tm<2, 1, 4, 4>(a, lds, stream));
+        } else if (wn == 4)
             err = tm == 1 ? launch_tm<1, 4, 4>(a, lds, stream)
                           : tm == 2 ? launch_tm<2, 4, 4>(a, lds, stream) : launch_tm<4, 4, 4>(a, lds, stream);
         else if (waves == 8)

@@ -15,8 +15,8 @@
 //     XOR-swizzled by row so that the 16-row operand reads are bank-conflict free;
 //   * every weight is read once and dequantised once, whatever M is: 2 vector ALU operations per weight
 //     instead of 1.2 + M/2 in the vector kernel.
-// Supports no g_idx and group sizes that are multiples of 128 (the tuned format); other cases use the
-// other kernels.
+// Supports no g_idx and group sizes that are multiples of 128 (the tuned format) or 64 / 32 (template GPU);
+// other cases use the other kernels.
 #pragma once
 
 #include "exchange.h"
@@ -80,11 +80,11 @@ __device__ __forceinline__ float load_device_scope(const float *p)
 }
 
 // Loads of one 128-k unit of one lane: 4 steps x 4 adjacent words, plus the unit's scales and zero word.
-template <int XROWS>  // XROWS: 16-row blocks of activations that travel with the weights (0: they are in LDS)
-struct UnitRegs {
+template <int XROWS, int GPU>  // XROWS: 16-row blocks of activations that travel with the weights (0: they are in LDS)
+struct UnitRegs {                // GPU: quantisation groups per unit (1: groups of 128 k or more; 2: 64; 4: 32)
     uint4 w[4];
-    uint2 sc;  // four fp16 scales as raw bits
-    uint32_t zb;
+    uint2 sc[GPU];  // four fp16 scales as raw bits, per group of the unit
+    uint32_t zb[GPU];
     u32x4_t xa[XROWS > 0 ? XROWS : 1][4];  // A operand per row block and k step
 };
 
@@ -97,9 +97,15 @@ struct UnitRegs {
 // eight, two per SIMD, so that the loads, LDS and scalar instructions of one overlap the arithmetic of the
 // other (3-11 % on the narrow and deep Llama layers; with more workgroups than compute units the co-resident
 // workgroups already do that, and eight wavefronts each measured 3-12 % slower).
-template <int TM, int WN, int WAVES>
+//
+// GPU: quantisation groups per 128-k unit.  1 serves every group size that is a multiple of 128; 2 and 4 serve
+// groups of 64 and 32 k: a unit then carries two or four (scale, zero) rows, the exact q - z of a 32-k step is
+// formed with its own group's zero point and the MFMA chain is scaled and restarted at every group boundary.
+template <int TM, int WN, int WAVES, int GPU = 1>
 __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
 {
+    static_assert(GPU == 1 || GPU == 2 || GPU == 4, "groups of >= 128, 64 or 32 k");
+    static_assert(GPU == 1 || TM <= 2, "small groups: up to two row blocks");
     static_assert(WAVES == 4 || (WAVES == 8 && WN == 1), "eight wavefronts only where they split the slice");
     constexpr int kWaves = WAVES;
     constexpr int kThreads = 64 * WAVES;
@@ -116,7 +122,7 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
     // the MFMA's k order, the same registers receive that step of the NEXT unit (from L2: a four-step lead is
     // enough), which leaves room for two wavefronts per SIMD.
     constexpr bool XSTEP = DIRECT && TM >= 4;
-    using Regs = UnitRegs<(DIRECT && !XSTEP) ? TM : 0>;
+    using Regs = UnitRegs<(DIRECT && !XSTEP) ? TM : 0, GPU>;
 
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int s_last;
@@ -165,10 +171,16 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
         for (int s = 0; s < 4; ++s)
             r.w[s] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(wrow + (size_t)s * 4 * N) +
                                                       voff_w);
-        const int grp = a.unit_group_shift >= 0 ? (uc >> a.unit_group_shift) : uc / a.units_per_group;
-        r.sc = *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(a.scales + (size_t)grp * N) + voff_s);
-        r.zb = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(a.qzeros + (size_t)grp * (N >> 3)) +
-                                                   voff_z);
+        const int grp0 = GPU > 1 ? uc * GPU
+                                 : (a.unit_group_shift >= 0 ? (uc >> a.unit_group_shift) : uc / a.units_per_group);
+#pragma unroll
+        for (int h = 0; h < GPU; ++h) {
+            const int grp = grp0 + h;
+            r.sc[h] =
+                *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(a.scales + (size_t)grp * N) + voff_s);
+            r.zb[h] = *reinterpret_cast<const uint32_t *>(
+                reinterpret_cast<const char *>(a.qzeros + (size_t)grp * (N >> 3)) + voff_z);
+        }
         if (DIRECT && !XSTEP) {
             const half_t *xrow = a.x + (size_t)uc * kUnitK;
 #pragma unroll
@@ -245,22 +257,26 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
     auto consume = [&](int u, const Regs &r, auto refill) {
         constexpr bool REFILL = decltype(refill)::value;  // XSTEP: fetch the next unit's A operands step by step
         const int j = u - u0;
+        constexpr int SPG = 4 / GPU;  // 32-k steps per quantisation group
         half2_t neg_lo[4], neg_hi[4], s2[4];
         float sf[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const uint32_t z = (r.zb >> (zshift + 4 * t)) & 15u;
-            const uint32_t zz = z | (z << 16);
-            neg_lo[t] = as_half2(zz | 0xE400E400u);         // (-(1024 + z)) x2
-            neg_hi[t] = as_half2((zz << 4) | 0xD400D400u);  // (-(64 + z)) x2
-            const uint32_t pair = t < 2 ? r.sc.x : r.sc.y;
-            const uint16_t sb = (uint16_t)((t & 1) ? (pair >> 16) : (pair & 0xffffu));
-            sf[t] = (float)__builtin_bit_cast(half_t, sb);
-            s2[t] = as_half2((uint32_t)sb | ((uint32_t)sb << 16));
-        }
         float4_t d[SCALE_B ? 1 : TM][4];
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
+            if (st % SPG == 0) {  // a group begins: its zero points and scales
+                const int h = st / SPG;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const uint32_t z = (r.zb[h] >> (zshift + 4 * t)) & 15u;
+                    const uint32_t zz = z | (z << 16);
+                    neg_lo[t] = as_half2(zz | 0xE400E400u);         // (-(1024 + z)) x2
+                    neg_hi[t] = as_half2((zz << 4) | 0xD400D400u);  // (-(64 + z)) x2
+                    const uint32_t pair = t < 2 ? r.sc[h].x : r.sc[h].y;
+                    const uint16_t sb = (uint16_t)((t & 1) ? (pair >> 16) : (pair & 0xffffu));
+                    sf[t] = (float)__builtin_bit_cast(half_t, sb);
+                    s2[t] = as_half2((uint32_t)sb | ((uint32_t)sb << 16));
+                }
+            }
             const uint32_t w[4] = {r.w[st].x, r.w[st].y, r.w[st].z, r.w[st].w};
             const int c = (j * 4 + st) * 4 + kg;  // 16-byte chunk of the activation row
             half8_t av[TM];
@@ -306,18 +322,19 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
                     if (SCALE_B)
                         acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av[i], b, acc[i][t], 0, 0, 0);
                     else
-                        d[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av[i], b, st == 0 ? zero : d[i][t], 0, 0, 0);
+                        d[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av[i], b, st % SPG == 0 ? zero : d[i][t], 0, 0,
+                                                                         0);
                 }
             }
-        }
-        if (!SCALE_B) {
+            if (!SCALE_B && st % SPG == SPG - 1) {  // the group is complete: scale its sum
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
+                    for (int t = 0; t < 4; ++t)
 #pragma unroll
-                    for (int rr = 0; rr < 4; ++rr)
-                        acc[i][t][rr] = __builtin_fmaf(sf[t], d[i][t][rr], acc[i][t][rr]);
+                        for (int rr = 0; rr < 4; ++rr)
+                            acc[i][t][rr] = __builtin_fmaf(sf[t], d[i][t][rr], acc[i][t][rr]);
+            }
         }
     };
 

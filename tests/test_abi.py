@@ -121,7 +121,9 @@ def test_default_dispatch_by_batch_size(lib):
     # act-order and group sizes the small-batch MFMA kernel does not take fall back
     assert q(8, 4096, 4096, 128, act_order=True).kernel == 1
     assert q(24, 4096, 4096, 128, act_order=True).kernel == 2
-    assert q(8, 4096, 4096, 64).kernel == 1
+    assert q(8, 4096, 4096, 64).kernel == 3 and q(8, 4096, 4096, 32).kernel == 3  # small groups: own variants
+    assert q(8, 4096, 4096, 16).kernel == 1 and q(8, 4096, 4096, 256).kernel == 3
+    assert q(40, 4096, 4096, 64).kernel == 2
     # an explicit request is honoured where the kernel supports the problem
     assert q(1, 4096, 4096, 128, plan=binding.Plan(kernel=2)).kernel == 2
     assert q(64, 4096, 4096, 128, plan=binding.Plan(kernel=3)).kernel == 3

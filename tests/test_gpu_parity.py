@@ -279,9 +279,34 @@ def test_small_batch_mfma_kernel_splits(B, split_k, M, tile):
     assert_within_band(out, ref, f"small-batch split={split_k} M={M} tile={tile}")
 
 
+@pytest.mark.parametrize("group", [64, 32])
+@pytest.mark.parametrize("M", [2, 8, 16, 17, 32])
+@pytest.mark.parametrize("K,N,split_k", [(1024, 200, 0), (2048, 1032, 3), (640, 72, 0), (128, 8, 0)])
+def test_small_batch_mfma_kernel_small_groups(B, M, K, N, split_k, group):
+    """Groups of 64 and 32 k: two / four (scale, zero) rows per 128-k unit, the MFMA chain scaled per group."""
+    assert B.gptq_w4a16_plan_query(M, K, N, group).kernel == 3, "the small-batch kernel is the default here"
+    case = workloads.make_case(M, K, N, group, seed=5 * K + N + M + group)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    out = run_gemm(B, case, group, B.Plan(kernel=3, split_k=split_k))
+    assert_within_band(out, ref, f"small-batch M={M} K={K} N={N} g={group}")
+
+
+@pytest.mark.parametrize("group", [64, 32])
+def test_small_batch_small_groups_one_hot_rows_bit_exact(B, group):
+    M, K, N = 12, 1024, 264
+    w = workloads.make_weights(K, N, group, seed=19 + group)
+    hot = [(131 * m + 7) % K for m in range(M)]
+    case = dict(w, x=workloads.one_hot_activations(M, K, hot))
+    w16 = oracle.dequant(w["qweight"], w["qzeros"], w["scales"], None, group)
+    out = run_gemm(B, case, group, B.Plan(kernel=3))
+    for m, j in enumerate(hot):
+        assert np.array_equal(out[m].view(np.uint16), w16[j].view(np.uint16)), f"row {m} (k={j})"
+
+
 def test_small_batch_request_falls_back_when_unsupported(B):
     # act-order and group sizes that are not multiples of 128 are served by the other kernels
-    for M, K, N, group, act in [(8, 512, 136, 64, False), (8, 512, 136, 128, True), (200, 512, 136, 128, False)]:
+    for M, K, N, group, act in [(8, 512, 136, 16, False), (8, 192, 136, 64, False), (40, 512, 136, 64, False),
+                                (8, 512, 136, 128, True), (200, 512, 136, 128, False)]:
         case = workloads.make_case(M, K, N, group, seed=M + N, act_order=act)
         ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], case["g_idx"], group)
         out = run_gemm(B, case, group, B.Plan(kernel=3))
