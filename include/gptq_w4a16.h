@@ -112,8 +112,8 @@ typedef struct gptq_w4a16_plan {
     int kernel;      /* 0 auto, 1 vector split-K kernel (any M, processed 16 rows at a time), 2 big-tile MFMA kernel,
                         3 small-batch MFMA kernel (M <= 128, processed 64 rows at a time; no g_idx,
                         group_size % 128 == 0; else falls back) */
-    int split_k;     /* number of K slices (all three kernels; the big-tile kernel splits by itself only on
-                        its 128x128 and 64x128 tiles); 0 auto */
+    int split_k;     /* number of K slices (all three kernels; the big-tile kernel splits by itself on every tile
+                        but 256x256); 0 auto */
     int tile;        /* vector kernel: columns per workgroup (16, 32, 64, 128 or 256);
                         small-batch MFMA kernel: columns per workgroup (64 or 256; anything else = auto);
                         MFMA kernel: tile id = rows x columns per workgroup (wavefront grid):

@@ -42,7 +42,7 @@ constexpr TileShape kTiles[11] = {
     {64, 128, 64, 0.46, true, 0.0, 3, {0.46, 0.72, 1.0}, 6.0, 6.0},
     {0, 0, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
     {0, 0, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
-    {128, 256, 64, 0.99, false, 1.31, 0, {0, 0, 0}, 0, 0},
+    {128, 256, 64, 0.99, true, 1.31, 0, {0, 0, 0}, 0, 0},
     {0, 0, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0},
     {0, 0, 64, 0.0, false, 0.0, 0, {0, 0, 0}, 0, 0}};
 constexpr int kNumTiles = 10;
@@ -83,6 +83,17 @@ double estimate_us(const Problem &p, int t, int split)
         if (slices > 1)
             us += 2.0 * wgs * ts.bm * ts.bn * sizeof(float) / (ts.scratch_tbps * 1e6);
         return us;
+    }
+    if (ts.pair_us > 0.0 && slices > 1) {
+        // K slices of the 128x256 tile, for few tiles under a deep K (M = 512 ... 1024 on the narrow layers): only
+        // with one workgroup per compute unit at most.  A stage takes 0.8 of its usual time while a quarter of
+        // the chip idles (clock), the slices' fp32 tiles go through scratch once each way - written by all
+        // workgroups at about 4 TB/s, read back by the last arriver of each tile alone at about 60 GB/s.
+        if (wgs > kComputeUnits)
+            return 1e30;
+        const double stage = ts.stage_us * (wgs <= 192.0 ? 0.8 : 1.0);
+        const double tile_bytes = (double)ts.bm * ts.bn * sizeof(float);
+        return 3.5 + sps * stage + 1.5 + 4.0 + wgs * tile_bytes / 4e6 + slices * tile_bytes / 6e4;
     }
     if (ts.pair_us > 0.0) {
         // whole waves of two workgroups per compute unit, then the rest: alone if it fits one per unit

@@ -212,7 +212,7 @@ def test_shape_limits_of_the_32_bit_offsets(lib):
 
 
 def test_big_tile_plan_is_well_formed_for_every_shape(lib):
-    """The big-tile kernel's automatic plan names an existing tile, splits K only on the two small tiles, never
+    """The big-tile kernel's automatic plan names an existing tile, splits K on every tile but 256x256, never
     into more slices than 64-k stages, and its scratch is covered by the workspace bound wherever the default
     dispatch would run it."""
     from paper_2511_19438_amd import binding, workloads
@@ -224,7 +224,9 @@ def test_big_tile_plan_is_well_formed_for_every_shape(lib):
             pl = binding.gptq_w4a16_plan_query(M, K, N, 128, plan=binding.Plan(kernel=2))
             assert pl.kernel == 2 and pl.tile in tile_dims, (M, K, N, pl.tile)
             assert 1 <= pl.split_k <= max(1, K // 64)
-            assert pl.split_k == 1 or pl.tile in (3, 5), (M, K, N, pl.tile, pl.split_k)
+            assert pl.split_k == 1 or pl.tile in (3, 5, 8), (M, K, N, pl.tile, pl.split_k)
+            if pl.tile == 8 and pl.split_k > 1:  # 128x256 tile: K slices only with one workgroup per compute unit
+                assert -(-M // 128) * -(-N // 256) * pl.split_k <= 256, (M, K, N, pl.split_k)
             if pl.split_k > 1 and binding.gptq_w4a16_plan_query(M, K, N, 128).kernel == 2:
                 bm, bn = tile_dims[pl.tile]
                 partial = pl.split_k * (-(-M // bm)) * (-(-N // bn)) * bm * bn * 4
