@@ -218,8 +218,9 @@ def main():
     print(json.dumps(line))
 
 
-def graph_us(torch, launches, reps=6):
-    """Mean microseconds per launch of a list of zero-argument launch functions, replayed as one HIP graph."""
+def graph_us(torch, launches, reps=4, batches=3):
+    """Microseconds per launch of a list of zero-argument launch functions, replayed as one HIP graph: the median
+    of `batches` timed batches of `reps` replays each (a single batch now and then catches a hiccup of the box)."""
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         for f in launches:
@@ -231,14 +232,17 @@ def graph_us(torch, launches, reps=6):
                 f()
         graph.replay()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for _ in range(reps):
-            graph.replay()
-        e1.record(stream)
-        torch.cuda.synchronize()
+        times = []
+        for _ in range(batches):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                graph.replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1) * 1e3 / (reps * len(launches)))
     del graph
-    return e0.elapsed_time(e1) * 1e3 / (reps * len(launches))
+    return sorted(times)[len(times) // 2]
 
 
 def sweep_tables(torch, B, workloads, layers):
