@@ -276,7 +276,17 @@ hipError_t launch_decode(const Problem &p, const DecodePlan &plan, void *workspa
             if (hipGetLastError() != hipSuccess)
                 return hipErrorLaunchFailure;
         }
-        const int flags = plan.flags | (p.x_perm ? decode::kGatherX : 0) | (waves == 8 ? decode::kEightWaves : 0);
+        // Group-level correction (decode::kGroupCorr): single row, groups of whole 128-k units, and a plan whose
+        // one slice gives every row lane whole groups (four chunks each per pair of steps) - otherwise lanes
+        // idle where the per-chunk kernel keeps them busy.  Measured: 4096x12288 7.6 -> 7.3 us, 4096x22016
+        // 12.0 -> 10.8; with K slices it was level or slower (8192x8192 9.9 -> 10.3), so those keep the
+        // per-chunk correction.
+        const int row_lanes = d.rw * waves / 4;
+        const bool group_corr = mb == 1 && !act && plan.flags == 0 && !p.x_perm && plan.chunk_rows == 4 &&
+                                p.group_size % 128 == 0 && plan.split_k == 1 &&
+                                plan.chunks_per_slice % (4 * row_lanes) == 0;
+        const int flags = plan.flags | (p.x_perm ? decode::kGatherX : 0) | (waves == 8 ? decode::kEightWaves : 0) |
+                          (group_corr ? decode::kGroupCorr : 0);
         hipError_t err;
         switch (mb) {
         case 1: err = decode::launch_mb<1>(a, d.lpr, plan.chunk_rows, act, flags, lds, stream); break;

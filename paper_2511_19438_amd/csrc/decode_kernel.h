@@ -21,6 +21,8 @@
 // wavefront load touches 4 rows x 256 contiguous bytes.
 #pragma once
 
+#include <type_traits>
+
 #include "exchange.h"
 #include "kernels.h"
 
@@ -148,6 +150,13 @@ constexpr int kGatherX = 16;
 // instructions of one overlap the vector arithmetic of the other (measured 3-8 % on the Llama GEMVs; sixteen
 // were twice as slow, and with more workgroups than compute units eight are 2-5 % slower than four).
 constexpr int kEightWaves = 32;
+// The bias / zero-point correction of the factored arithmetic once per quantisation group (128 k = four chunks)
+// instead of once per 32-k chunk: a lane then walks the four chunks of ONE group in two consecutive pipeline steps
+// (chunks 4g .. 4g+3, two per step), keeps the matrix-unit sums running across them and corrects with the
+// group's activation sums - the conversions of the four zero points and scales and the two fused multiply-adds
+// per column are paid once per 64 packed words instead of once per 16.  Single row, plain format, group sizes
+// that are multiples of 128, slices of whole groups.
+constexpr int kGroupCorr = 64;
 
 template <int MB, int LPR, int R, bool ACT, int ABL = 0>
 __global__ __launch_bounds__((ABL & kEightWaves) ? 512 : 256) void decode_kernel(const Args a)
@@ -155,6 +164,9 @@ __global__ __launch_bounds__((ABL & kEightWaves) ? 512 : 256) void decode_kernel
     static_assert(ABL == 0 || (!ACT && MB < 8), "the ablation variants exist for the plain format at small batch");
     static_assert(!(ABL & kMatrixDot) || MB <= 4, "the 4x4x4 matrix product carries four batch rows");
     static_assert(!(ABL & kEightWaves) || (MB == 1 && !ACT), "eight wavefronts: single row, plain format");
+    constexpr bool GC = (ABL & kGroupCorr) != 0;
+    static_assert(!GC || (MB == 1 && !ACT && R == 4 && (ABL & kMatrixDot) && !(ABL & 7)),
+                  "group-level correction: single row, plain format, matrix-unit loop");
     constexpr int kWaves = (ABL & kEightWaves) ? 8 : 4;
     constexpr int kThreads = 64 * kWaves;
     constexpr int RL = 64 / LPR;          // row lanes per wavefront
@@ -210,9 +222,13 @@ __global__ __launch_bounds__((ABL & kEightWaves) ? 512 : 256) void decode_kernel
     // load costs no 64-bit vector arithmetic: the R packed rows of a chunk differ only in the base.
     const int n0c = min(n0, N - 4);
     const uint32_t *wslice = a.qweight + (size_t)c0 * R * N;  // first packed row of the slice
-    auto lane_chunk = [&](int t, int j) { return t * STEP + j * RW + rid; };  // slice-relative, step t
+    // slice-relative chunk of this lane in step t (GC: the four chunks of group (t / 2) * RW + rid over two steps)
+    auto lane_chunk = [&](int t, int j) {
+        return GC ? 4 * ((t >> 1) * RW + rid) + 2 * (t & 1) + j : t * STEP + j * RW + rid;
+    };
     using Regs = StepRegs<R, UNROLL>;
-    auto issue = [&](int t, Regs &r) {
+    auto issue = [&](int t, Regs &r, auto odd_tag) {
+        constexpr bool ODD = decltype(odd_tag)::value;  // GC: the group's scales and zeros travel with the even step
 #pragma unroll
         for (int j = 0; j < UNROLL; ++j) {
             const int ul = min(lane_chunk(t, j), nchunks - 1);
@@ -221,7 +237,7 @@ __global__ __launch_bounds__((ABL & kEightWaves) ? 512 : 256) void decode_kernel
             for (int rr = 0; rr < R; ++rr)
                 r.wq[j][rr] = *reinterpret_cast<const uint4 *>(
                     reinterpret_cast<const char *>(wslice + (size_t)rr * N) + woff);
-            if (!ACT) {
+            if (!ACT && !(GC && (ODD || j > 0))) {
                 const int u = c0 + ul;
                 const int grp = a.chunk_group_shift >= 0 ? (u >> a.chunk_group_shift) : (u * R) / a.rows_per_group;
                 r.sc[j] = *reinterpret_cast<const half4_t *>(reinterpret_cast<const char *>(a.scales) +
@@ -276,20 +292,23 @@ __global__ __launch_bounds__((ABL & kEightWaves) ? 512 : 256) void decode_kernel
             // sums of x over the k that get bias 1024 / bias 64, added over the R rows of the chunk
             float s_lo = ((float)h[0] + (float)h[4]) + ((float)h[2] + (float)h[6]);
             float s_hi = ((float)h[1] + (float)h[5]) + ((float)h[3] + (float)h[7]);
+            constexpr int SUMROWS = GC ? 16 : R;  // packed rows whose sums travel together: a chunk, or a group
 #pragma unroll
-            for (int o = 1; o < R; o <<= 1) {
+            for (int o = 1; o < SUMROWS; o <<= 1) {
                 s_lo += __shfl_xor(s_lo, o, 64);
                 s_hi += __shfl_xor(s_hi, o, 64);
             }
-            if (i < items && (row & (R - 1)) == 0)
-                xc[(size_t)m * nchunks + row / R] = make_float2(1024.f * s_lo + 64.f * s_hi, s_lo + s_hi);
+            if (i < items && (row & (SUMROWS - 1)) == 0)
+                xc[(size_t)m * nchunks + row / SUMROWS] = make_float2(1024.f * s_lo + 64.f * s_hi, s_lo + s_hi);
         }
     };
 
+    const std::integral_constant<bool, false> even_step;
+    const std::integral_constant<bool, true> odd_step;
     Regs ra, rb;
     {
         const half8_t h0 = x_load(tid);
-        issue(0, ra);  // the weights are in flight while the activations are staged
+        issue(0, ra, even_step);  // the weights are in flight while the activations are staged
         x_store(tid, h0);
         for (int i0 = kThreads; i0 < items; i0 += kThreads)
             x_store(i0 + tid, x_load(i0 + tid));
@@ -322,7 +341,52 @@ __global__ __launch_bounds__((ABL & kEightWaves) ? 512 : 256) void decode_kernel
     const NibbleMagic magic;
 
     // dequantise and contract the chunks held in `r`
-    auto consume = [&](int t, const Regs &r) {
+    float4_t gdot[4];   // GC: the matrix-unit sums of the group being walked
+    float gzf[4], gsf[4];  // GC: its zero points and scales
+    auto consume = [&](int t, const Regs &r, auto odd_tag) {
+        constexpr bool ODD = decltype(odd_tag)::value;
+        if constexpr (GC) {
+            const int gi = (t >> 1) * RW + rid;          // slice-relative group of this lane
+            const bool valid = gi < (nchunks >> 2);
+            if (!ODD) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    gdot[c] = float4_t{0.f, 0.f, 0.f, 0.f};
+                    gzf[c] = (float)((r.zb[0] >> (zshift + 4 * c)) & 15u);
+                    gsf[c] = valid ? (float)r.sc[0][c] : 0.f;  // a clamped group contributes nothing
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < UNROLL; ++j) {
+                const int ul = min(lane_chunk(t, j), nchunks - 1);
+                const half_t *xchunk = xs + ul * (R * 8);
+#pragma unroll
+                for (int rr = 0; rr < R; ++rr) {
+                    const uint32_t w[4] = {r.wq[j][rr].x, r.wq[j][rr].y, r.wq[j][rr].z, r.wq[j][rr].w};
+                    const uint4 xv = *reinterpret_cast<const uint4 *>(xchunk + rr * 8);
+                    const half4_t a01 = __builtin_bit_cast(half4_t, make_uint2(xv.x, xv.y));
+                    const half4_t a23 = __builtin_bit_cast(half4_t, make_uint2(xv.z, xv.w));
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        half2_t d[4];
+                        biased_codes(w[c], magic, d);
+                        const half4_t b01 = __builtin_bit_cast(half4_t, make_uint2(as_u32(d[0]), as_u32(d[1])));
+                        const half4_t b23 = __builtin_bit_cast(half4_t, make_uint2(as_u32(d[2]), as_u32(d[3])));
+                        gdot[c] = __builtin_amdgcn_mfma_f32_4x4x4f16(a01, b01, gdot[c], 0, 0, 0);
+                        gdot[c] = __builtin_amdgcn_mfma_f32_4x4x4f16(a23, b23, gdot[c], 0, 0, 0);
+                    }
+                }
+            }
+            if (ODD) {
+                const float2 bs = xc[min(gi, (nchunks >> 2) - 1)];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float tt = __builtin_fmaf(-gzf[c], bs.y, gdot[c][0] - bs.x);  // sum_k x_k (q_k - z)
+                    acc[0][c] = __builtin_fmaf(gsf[c], tt, acc[0][c]);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int j = 0; j < UNROLL; ++j) {
             const bool valid = lane_chunk(t, j) < nchunks;
@@ -475,7 +539,8 @@ __global__ __launch_bounds__((ABL & kEightWaves) ? 512 : 256) void decode_kernel
         // consumed.  Every wavefront runs the same number of steps (lanes past the end of the slice load
         // clamped chunks and add nothing); the steady-state loop issues unconditionally and the last one
         // or two steps are peeled, so that no branch separates a load from its use.
-        const int nsteps = (nchunks + STEP - 1) / STEP;
+        // (GC: two steps per group, RW groups per pair of steps)
+        const int nsteps = GC ? 2 * (((nchunks >> 2) + RW - 1) / RW) : (nchunks + STEP - 1) / STEP;
         int t = 0;
         // The step boundary: everything a step adds to the accumulators is computed before the loads of
         // the step after next are issued (the empty asm orders the arithmetic, the scheduling barrier the
@@ -487,21 +552,21 @@ __global__ __launch_bounds__((ABL & kEightWaves) ? 512 : 256) void decode_kernel
             __builtin_amdgcn_sched_barrier(0);
         };
         while (t + 2 < nsteps) {
-            issue(t + 1, rb);
-            consume(t, ra);
+            issue(t + 1, rb, odd_step);
+            consume(t, ra, even_step);
             step_boundary();
-            issue(t + 2, ra);
-            consume(t + 1, rb);
+            issue(t + 2, ra, even_step);
+            consume(t + 1, rb, odd_step);
             step_boundary();
             t += 2;
         }
         if (t + 2 == nsteps) {
-            issue(t + 1, rb);
-            consume(t, ra);
+            issue(t + 1, rb, odd_step);
+            consume(t, ra, even_step);
             step_boundary();
-            consume(t + 1, rb);
+            consume(t + 1, rb, odd_step);
         } else {
-            consume(t, ra);
+            consume(t, ra, even_step);
         }
     }
 

@@ -105,6 +105,10 @@ hipError_t dispatch(const Args &a, int lpr, int chunk_rows, bool act, int varian
     if (chunk_rows == 4) {
         // Up to four batch rows the inner loop contracts on the matrix unit (kMatrixDot): measured 3-6 % faster
         // than v_dot2_f32_f16 at M = 1, which stays as a comparison switch and for the larger batches.
+        if constexpr (MB == 1) {
+            if (!vector_dot && (variant & kGroupCorr))
+                return launch_lpr_waves<MB, kMatrixDot | kGroupCorr>(a, lpr, eight_waves, lds_bytes, stream);
+        }
         if constexpr (MB <= 4) {
             if (!vector_dot)
                 return launch_lpr_waves<MB, kMatrixDot>(a, lpr, eight_waves, lds_bytes, stream);

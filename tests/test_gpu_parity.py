@@ -689,3 +689,17 @@ def test_activations_with_large_mean_and_outliers(B, M, K, N, plan_args, kind):
     assert worst(own) <= 0.5, f"{kind}: err/tol = {worst(own):.3f} against the kernel's own definition of W"
     if kind != "huge_offset":
         assert worst(other) <= 8.0, f"{kind}: err/tol = {worst(other):.3f} against the other definition of W"
+
+
+@pytest.mark.parametrize("K,N,tile", [(4096, 1000, 64), (4096, 2072, 128), (2048, 520, 32), (8192, 776, 256),
+                                      (4096, 1000, 0), (1024, 264, 64)])
+def test_single_row_group_level_correction(B, K, N, tile):
+    """Unsplit single-row plans whose slice gives every row lane whole 128-k groups run the variant that corrects
+    bias and zero point once per group (two pipeline steps per group); others the per-chunk kernel.  Both against
+    the oracle, ragged last column tile included, and groups of 256 k."""
+    for group in (128, 256):
+        case = workloads.make_case(1, K, N, group, seed=K + N + tile + group)
+        ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+        plan = B.Plan(kernel=1, tile=tile, split_k=1) if tile else None
+        out = run_gemm(B, case, group, plan)
+        assert_within_band(out, ref, f"single row K={K} N={N} tile={tile} g={group}")
