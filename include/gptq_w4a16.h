@@ -72,8 +72,11 @@ enum gptq_status {
  * not be zeroed (unlike the accumulate-by-atomicAdd contract of Eq. 9-10).
  * By default M = 1 runs the bandwidth-bound split-K vector kernel, 2 <= M <= 32 a small-batch
  * MFMA kernel with the same split-K decomposition (when the format allows: no g_idx,
- * group_size % 128 == 0; otherwise the vector kernel up to M = 16), larger M the big-tile fp16
- * MFMA kernel (with K slices where the output tiles alone would not fill the chip).
+ * group_size % 128 == 0 or 64 / 32; otherwise the vector kernel up to M = 16), 33 <= M <= 64
+ * (and 17-32 or 65-128 rows on the layer shapes where it measured faster) a mid-batch MFMA
+ * kernel in which every wavefront streams its own share of the K slice (no g_idx, K and
+ * group_size multiples of 64), larger M the big-tile fp16 MFMA kernel (with K slices where
+ * the output tiles alone would not fill the chip).
  * Accumulation is in fp32; the result differs from the exact sum by fp32 reassociation
  * and the final fp16 rounding only.  The same inputs give bit-identical outputs on every
  * call (no floating point atomics are used).
@@ -88,13 +91,14 @@ GPTQ_API int gptq_w4a16_gemm(const void *x, const void *qweight, const void *qze
  * results as gptq_w4a16_gemm, but the split-K scratch (partial sums and arrival counters) is a fixed block of
  * GPTQ_STATIC_SCRATCH_BYTES inside the library's device image: every GPU the library runs on holds it until the
  * process ends, and the call makes no hipMalloc / hipFree and ignores gptq_w4a16_set_workspace().  A problem
- * whose plan needs more scratch returns GPTQ_STATIC_SCRATCH_EXCEEDED and enqueues nothing (needs are at most
- * 256 KiB + 4 * slices * M * N bytes; every Llama-7B/70B layer shape up to M = 2048 fits).  The first call on a
+ * whose plan needs more scratch returns GPTQ_STATIC_SCRATCH_EXCEEDED and enqueues nothing (needs are
+ * 256 KiB + 4 * slices * M * N bytes where the plan splits K, which it does only while the output is small; the
+ * largest need among the Llama-7B/70B layer shapes for M up to 2048 is 40.3 MiB, at 512 x 8192 x 10240).  The first call on a
  * device also enqueues one small kernel on `stream` that clears the arrival counters.  All calls on one GPU share
  * the block: calls that overlap in time on one GPU (different streams) race, as do a call here and a graph replay
  * that uses it.
  */
-#define GPTQ_STATIC_SCRATCH_BYTES (32u << 20)
+#define GPTQ_STATIC_SCRATCH_BYTES (48u << 20)
 GPTQ_API int gptq_w4a16_gemm_static(const void *x, const void *qweight, const void *qzeros, const void *scales,
                                     const void *g_idx, void *out, int M, int K, int N, int group_size,
                                     gptq_stream_t stream);
@@ -111,11 +115,15 @@ GPTQ_API int gptq_w4a16_gemm_static(const void *x, const void *qweight, const vo
 typedef struct gptq_w4a16_plan {
     int kernel;      /* 0 auto, 1 vector split-K kernel (any M, processed 16 rows at a time), 2 big-tile MFMA kernel,
                         3 small-batch MFMA kernel (M <= 128, processed 64 rows at a time; no g_idx,
-                        group_size % 128 == 0; else falls back) */
-    int split_k;     /* number of K slices (all three kernels; the big-tile kernel splits by itself on every tile
+                        group_size % 128 == 0; else falls back),
+                        4 mid-batch streaming MFMA kernel (M <= 128; no g_idx, K % 64 == 0, group_size % 64 == 0;
+                        else falls back) */
+    int split_k;     /* number of K slices (all four kernels; the big-tile kernel splits by itself on every tile
                         but 256x256); 0 auto */
     int tile;        /* vector kernel: columns per workgroup (16, 32, 64, 128 or 256);
                         small-batch MFMA kernel: columns per workgroup (64 or 256; anything else = auto);
+                        mid-batch MFMA kernel: columns per workgroup (64 or 128; anything else = auto; more than
+                        64 rows always use 64);
                         MFMA kernel: tile id = rows x columns per workgroup (wavefront grid):
                         1 256x256 (1x4), 3 128x128 (2x2), 5 64x128 (1x4), 8 128x256 (1x4, two workgroups
                         per compute unit); 0 auto; any other id is GPTQ_INVALID_ARG */
@@ -169,8 +177,8 @@ GPTQ_API int gptq_w4a16_gemm_prepared(const void *x, const void *qweight_sorted,
 /*
  * Host-only: what gptq_w4a16_gemm_plan(..., request) would run for a problem of this shape.
  * `act_order` non-zero means a g_idx array would be passed; `request` may be NULL (automatic).
- * On success *resolved holds the kernel id (1, 2 or 3, never 0), its number of K slices and its tile
- * (vector and small-batch kernels: columns per workgroup; big-tile MFMA kernel: tile id).  Touches no
+ * On success *resolved holds the kernel id (1 to 4, never 0), its number of K slices and its tile
+ * (vector, small-batch and mid-batch kernels: columns per workgroup; big-tile MFMA kernel: tile id).  Touches no
  * device.  Errors as for gptq_w4a16_gemm_plan's shape and plan checks.
  */
 GPTQ_API int gptq_w4a16_plan_query(int M, int K, int N, int group_size, int act_order,

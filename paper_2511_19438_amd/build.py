@@ -38,6 +38,7 @@ def units():
            ("decode.hip", "decode.o", []),
            ("prefill.hip", "prefill.o", []),
            ("skinny.hip", "skinny.o", []),
+           ("mid.hip", "mid.o", []),
            ("act_order.hip", "act_order.o", []),
            ("probe.hip", "probe.o", [])]
     for mb in DECODE_BATCHES:

@@ -79,6 +79,14 @@ double estimate_us(const Problem &p, const Derived &d, int cols_per_wg, int chun
     double t = 4.2 + std::cbrt(hbm * hbm * hbm + cu * cu * cu);
     if (slices > 1)
         t += 0.8;
+    // Unsplit single-row plans that qualify for the group-level correction (see launch_decode) and keep more than
+    // half of the compute units busy measured about a microsecond under this estimate (8192x10240: 64-column
+    // tiles unsplit 11.0 us against 12.1 for the 128-column tiles in three slices the estimate used to prefer).
+    const int waves = decode_waves(batch_template(m), act, chunk_rows, (long long)wgs);
+    if (m == 1 && !act && chunk_rows == 4 && slices == 1 && p.group_size % 128 == 0 && wgs > 128.0 &&
+        cols_per_wg >= 64 &&
+        cps % (4 * d.rw * waves / 4) == 0)
+        t -= 1.0;
     if (wgs > 256.0)
         t += 0.03 * hbm;
     return t;

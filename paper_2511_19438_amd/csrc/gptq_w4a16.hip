@@ -28,7 +28,7 @@ std::vector<void *> g_retired[kMaxDevices];  // outgrown library-owned blocks, s
 // Scratch of gptq_w4a16_gemm_static(): a fixed block in every device's copy of the code object, for callers
 // that may not allocate.  The array's name is only a host-side handle; its device address is looked up once
 // per device (static_scratch_ptr) and that pointer is what kernels and fills receive.
-constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+constexpr size_t kStaticScratchBytes = GPTQ_STATIC_SCRATCH_BYTES;
 void *g_static_ptr[kMaxDevices] = {};
 
 }  // namespace
@@ -136,9 +136,12 @@ int acquire_workspace(size_t bytes, hipStream_t stream, void **out)
 
 // Default kernel by batch size, from measurement on Llama-shaped layers.  A single row is streamed fastest
 // by the vector kernel.  From two rows on the small-batch MFMA kernel wins: its time is nearly flat up to 16
-// rows and grows slowly to 32, where the vector kernel pays for every weight once per batch row.  Past 32
-// rows it would run as two launches, which the big-tile MFMA kernel with K slices beats on every Llama shape
-// measured (33-48 rows: 14-28 us against 18-37 us).
+// rows and grows slowly to 32, where the vector kernel pays for every weight once per batch row.  From 33 to
+// 64 rows the mid-batch streaming kernel is the fastest on every Llama shape measured (10-40 % ahead of the
+// big-tile kernel with K slices); it also takes 17-32 rows on wide or very deep layers (3-17 % ahead of the
+// small-batch kernel, 2-12 % behind it on narrow ones) and 65-128 rows where its 64-column tiles give between half
+// and all of the compute units one workgroup each, or K is deep (1-24 % ahead of the big-tile kernel; 3-18 %
+// behind it on 4096x4096 and on layers whose tiles make a second, partly filled round).
 constexpr int kVectorMaxM = 1;
 constexpr int kSmallBatchAutoMaxM = 32;
 
@@ -149,11 +152,24 @@ bool small_batch_by_default(const Problem &p)
     return p.M <= kSmallBatchAutoMaxM;
 }
 
+bool mid_batch_by_default(const Problem &p)
+{
+    if (!mid_supported(p) || p.M <= 16)
+        return false;
+    const long long tiles64 = (p.N + 63) / 64;
+    if (p.M <= 32)
+        return tiles64 >= 160 || (long long)p.K * p.N >= (1ll << 27);
+    if (p.M <= 64)
+        return true;
+    return tiles64 <= 256 && (tiles64 >= 128 || p.K >= 8192);
+}
+
 // What a call resolves to: the kernel and its decomposition, after the automatic choices.
 struct Resolved {
-    int kernel;  // 1 vector, 2 big-tile MFMA, 3 small-batch MFMA
+    int kernel;  // 1 vector, 2 big-tile MFMA, 3 small-batch MFMA, 4 mid-batch streaming MFMA
     DecodePlan decode;
     SkinnyPlan skinny;
+    MidPlan mid;
     PrefillPlan prefill;
 };
 
@@ -164,12 +180,16 @@ Resolved resolve(const Problem &p, const gptq_w4a16_plan_t *plan)
     if (kernel == 0) {
         if (p.M <= kVectorMaxM)
             kernel = 1;
+        else if (mid_batch_by_default(p))
+            kernel = 4;
         else if (small_batch_by_default(p))
             kernel = 3;
         else
             kernel = (p.M <= kDecodeMaxM) ? 1 : 2;
     }
     if (kernel == 3 && !skinny_supported(p))
+        kernel = (p.M <= kDecodeMaxM) ? 1 : 2;
+    if (kernel == 4 && !mid_supported(p))
         kernel = (p.M <= kDecodeMaxM) ? 1 : 2;
     if (kernel == 2 && !prefill_supported(p))
         kernel = 1;
@@ -190,6 +210,10 @@ Resolved resolve(const Problem &p, const gptq_w4a16_plan_t *plan)
         r.skinny.cols_per_wg = plan ? plan->tile : 0;
         r.skinny.split_k = plan ? plan->split_k : 0;
         skinny_make_plan(p, r.skinny);
+    } else if (kernel == 4) {
+        r.mid.cols_per_wg = plan ? plan->tile : 0;
+        r.mid.split_k = plan ? plan->split_k : 0;
+        mid_make_plan(p, r.mid);
     } else {
         r.prefill.tile = plan ? plan->tile : 0;
         r.prefill.split_k = plan ? plan->split_k : 0;
@@ -204,6 +228,8 @@ size_t scratch_bytes(const Problem &p, const Resolved &r)
         return decode_workspace_bytes(p, r.decode);
     if (r.kernel == 3)
         return skinny_workspace_bytes(p, r.skinny);
+    if (r.kernel == 4)
+        return mid_workspace_bytes(p, r.mid);
     return prefill_workspace_bytes(p, r.prefill);  // 0 unless K is split
 }
 
@@ -214,6 +240,8 @@ int launch_resolved(const Problem &p, const Resolved &r, void *ws, hipStream_t s
         err = launch_decode(p, r.decode, ws, stream);
     else if (r.kernel == 3)
         err = launch_skinny(p, r.skinny, ws, stream);
+    else if (r.kernel == 4)
+        err = launch_mid(p, r.mid, ws, stream);
     else
         err = launch_prefill(p, r.prefill, ws, stream);
     return err == hipSuccess ? GPTQ_OK : GPTQ_HIP_ERROR;
@@ -241,7 +269,7 @@ int check_plan(const gptq_w4a16_plan_t *plan)
 {
     if (!plan)
         return GPTQ_OK;
-    if (plan->kernel < 0 || plan->kernel > 3 || plan->split_k < 0 || plan->tile < 0)
+    if (plan->kernel < 0 || plan->kernel > 4 || plan->split_k < 0 || plan->tile < 0)
         return GPTQ_INVALID_ARG;
     // the ablation switches belong to the vector kernel
     if (plan->flags < 0 || plan->flags > 15 || (plan->flags != 0 && plan->kernel != 1))
@@ -352,6 +380,9 @@ int gptq_w4a16_plan_query(int M, int K, int N, int group_size, int act_order, co
     } else if (r.kernel == 3) {
         out.split_k = r.skinny.split_k;
         out.tile = r.skinny.cols_per_wg;
+    } else if (r.kernel == 4) {
+        out.split_k = r.mid.split_k;
+        out.tile = r.mid.cols_per_wg;
     } else {
         out.split_k = r.prefill.split_k;
         out.tile = r.prefill.tile;
@@ -531,12 +562,12 @@ size_t gptq_w4a16_workspace_bytes(int M, int K, int N, int group_size)
         if (sk > bytes)
             bytes = sk;
     }
-    // the big-tile kernel splits K on few-tile shapes; counted where the default dispatch picks it
+    // the big-tile and mid-batch kernels split K on few-tile shapes; counted where the default dispatch picks them
     for (int act = 0; act < 2; ++act) {
         p.g_idx = act ? &dummy : nullptr;
         const Resolved r = resolve(p, nullptr);
-        if (r.kernel == 2) {
-            const size_t pf = prefill_workspace_bytes(p, r.prefill);
+        if (r.kernel == 2 || r.kernel == 4) {
+            const size_t pf = scratch_bytes(p, r);
             if (pf > bytes)
                 bytes = pf;
         }
@@ -588,7 +619,7 @@ const char *gptq_w4a16_strerror(int code)
     case GPTQ_HIP_ERROR: return "a HIP call or kernel launch failed";
     case GPTQ_WORKSPACE_TOO_SMALL: return "caller-set workspace is too small for this problem";
     case GPTQ_STATIC_SCRATCH_EXCEEDED:
-        return "problem needs more split-K scratch than the 32 MiB static block of gptq_w4a16_gemm_static";
+        return "problem needs more split-K scratch than the 48 MiB static block of gptq_w4a16_gemm_static";
     default: return "unknown status code";
     }
 }

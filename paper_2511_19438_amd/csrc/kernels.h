@@ -72,6 +72,18 @@ void skinny_make_plan(const Problem &p, SkinnyPlan &plan);
 size_t skinny_workspace_bytes(const Problem &p, const SkinnyPlan &plan);
 hipError_t launch_skinny(const Problem &p, const SkinnyPlan &plan, void *workspace, hipStream_t stream);
 
+// ---- mid batch: streaming MFMA kernel, every wavefront on its own share of the K slice, M <= 128 ----
+constexpr int kMidMaxM = 128;
+struct MidPlan {
+    int cols_per_wg;       // 64 or 128 (two or four 32-column n-blocks per wavefront); 0 = choose
+    int split_k;           // number of K slices across workgroups (0 = choose)
+    int stages_per_slice;  // 64-k stages per slice
+};
+bool mid_supported(const Problem &p);
+void mid_make_plan(const Problem &p, MidPlan &plan);
+size_t mid_workspace_bytes(const Problem &p, const MidPlan &plan);
+hipError_t launch_mid(const Problem &p, const MidPlan &plan, void *workspace, hipStream_t stream);
+
 // ---- prefill: fp16 MFMA kernel ----
 struct PrefillPlan {
     int tile;     // tile configuration id (1-based), 0 = auto

@@ -78,7 +78,7 @@ def test_plan_validation(lib):
     from paper_2511_19438_amd import binding
 
     p = ctypes.c_void_p(0x1000)
-    bad = binding.Plan(kernel=4)
+    bad = binding.Plan(kernel=5)
     assert lib.gptq_w4a16_gemm_plan(p, p, p, p, None, p, 1, 128, 8, 128, None, ctypes.byref(bad)) == -1
     # the ablation switches belong to the vector kernel, have three bits and exist for small plain problems
     for bad in (binding.Plan(flags=1), binding.Plan(kernel=2, flags=1), binding.Plan(kernel=1, flags=16),
@@ -116,17 +116,28 @@ def test_default_dispatch_by_batch_size(lib):
     from paper_2511_19438_amd import binding
 
     q = binding.gptq_w4a16_plan_query
-    assert [q(M, 4096, 4096, 128).kernel for M in (1, 2, 3, 16, 32, 33, 48, 49, 2048)] == [1, 3, 3, 3, 3, 2, 2, 2, 2]
-    assert [q(M, 4096, 22016, 128).kernel for M in (32, 33, 48)] == [3, 2, 2]
+    assert [q(M, 4096, 4096, 128).kernel for M in (1, 2, 3, 16, 32, 33, 64, 65, 128, 129, 2048)] == \
+        [1, 3, 3, 3, 3, 4, 4, 2, 2, 2, 2]
+    # the mid-batch streaming kernel: 33-64 rows everywhere, 17-32 rows on wide or very deep layers, 65-128 rows
+    # where its 64-column tiles give half to all of the compute units a workgroup or K is deep
+    assert [q(M, 4096, 22016, 128).kernel for M in (16, 17, 32, 33, 64, 65, 128)] == [3, 4, 4, 4, 4, 2, 2]
+    assert [q(M, 4096, 12288, 128).kernel for M in (16, 17, 64, 65, 128, 129)] == [3, 4, 4, 4, 4, 2]
+    assert [q(M, 28672, 8192, 128).kernel for M in (16, 24, 100)] == [3, 4, 4]
+    assert [q(M, 11008, 4096, 128).kernel for M in (24, 48, 100)] == [3, 4, 4]
     # act-order and group sizes the small-batch MFMA kernel does not take fall back
     assert q(8, 4096, 4096, 128, act_order=True).kernel == 1
     assert q(24, 4096, 4096, 128, act_order=True).kernel == 2
     assert q(8, 4096, 4096, 64).kernel == 3 and q(8, 4096, 4096, 32).kernel == 3  # small groups: own variants
     assert q(8, 4096, 4096, 16).kernel == 1 and q(8, 4096, 4096, 256).kernel == 3
-    assert q(40, 4096, 4096, 64).kernel == 2
+    assert q(40, 4096, 4096, 64).kernel == 4 and q(40, 4096, 4096, 32).kernel == 2  # groups of 64 k: one stage each
+    assert q(40, 4096, 4096, 128, act_order=True).kernel == 2
+    assert q(40, 4096 + 32, 4096, 4096 + 32).kernel == 2   # K must be a multiple of 64
     # an explicit request is honoured where the kernel supports the problem
     assert q(1, 4096, 4096, 128, plan=binding.Plan(kernel=2)).kernel == 2
     assert q(64, 4096, 4096, 128, plan=binding.Plan(kernel=3)).kernel == 3
+    assert q(8, 4096, 4096, 128, plan=binding.Plan(kernel=4)).kernel == 4
+    assert q(200, 4096, 4096, 128, plan=binding.Plan(kernel=4)).kernel == 2
+    assert q(8, 4096, 4096, 128, act_order=True, plan=binding.Plan(kernel=4)).kernel == 1
     assert q(8, 4096, 4096, 128, act_order=True, plan=binding.Plan(kernel=3)).kernel == 1
 
 

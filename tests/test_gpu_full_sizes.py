@@ -130,6 +130,15 @@ def test_config4_llama70b(B, shape_index, M):
     check_sampled(B, M, sh.K, sh.N, workloads.case_seed(4, shape_index))
 
 
+@pytest.mark.parametrize("family,shape_index", [(7, 0), (7, 1), (7, 2), (7, 3), (70, 0), (70, 2), (70, 3)])
+@pytest.mark.parametrize("M", [24, 64, 128])
+def test_mid_batch_sweep_at_full_size(B, family, shape_index, M):
+    """Mid batch (17-128 rows) on the Llama shapes, automatic plan: the mid-batch streaming kernel where the
+    dispatch picks it (many workgroups, two rounds of them on the widest layer), the others elsewhere."""
+    sh = (workloads.LLAMA_7B if family == 7 else workloads.LLAMA_70B)[shape_index]
+    check_sampled(B, M, sh.K, sh.N, 7000 + 10 * shape_index + M)
+
+
 def test_dequant_full_size_70b_down_projection_is_bit_exact_on_samples(B):
     sh = workloads.LLAMA_70B[3]
     w, d = device_weights(sh.K, sh.N, workloads.case_seed(4, 3))

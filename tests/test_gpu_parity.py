@@ -313,9 +313,64 @@ def test_small_batch_request_falls_back_when_unsupported(B):
         assert_within_band(out, ref, f"fallback M={M} g={group} act={act}")
 
 
+# ------------------------------------------------------------------ GEMM, mid-batch streaming MFMA kernel
+
+MID_SHAPES = [
+    # (K, N, group): several column tiles with a ragged last one; stage counts that are not multiples of three or of
+    # the wavefront count (a single stage included); groups of one, two, three and four 64-k stages
+    (1024, 200, 128),
+    (2048, 1032, 128),
+    (640, 72, 64),
+    (1536, 328, 256),
+    (64, 8, 64),
+    (1152, 136, 192),
+]
+
+
+@pytest.mark.parametrize("tile", [64, 128])
+@pytest.mark.parametrize("M", [1, 17, 32, 33, 49, 64, 65, 100, 128])
+@pytest.mark.parametrize("K,N,group", MID_SHAPES)
+def test_mid_batch_kernel_matches_oracle(B, M, K, N, group, tile):
+    case = workloads.make_case(M, K, N, group, seed=3 * K + N + M)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    plan = B.Plan(kernel=4, tile=tile)
+    res = B.gptq_w4a16_plan_query(M, K, N, group, False, plan)
+    assert res.kernel == 4 and res.tile == (tile if M <= 64 else 64)  # four row blocks: 64-column tiles only
+    out = run_gemm(B, case, group, plan)
+    assert_within_band(out, ref, f"mid-batch M={M} K={K} N={N} g={group} tile={tile}")
+
+
+@pytest.mark.parametrize("tile", [64, 128])
+@pytest.mark.parametrize("split_k", [1, 2, 3, 5, 32])
+@pytest.mark.parametrize("M", [40, 64, 90])
+def test_mid_batch_kernel_splits(B, split_k, M, tile):
+    """K slices across workgroups (ragged last slice, more slices than a wavefront has stages), combined through
+    scratch; twice in a row: the arrival counters must be back at zero and the result the same bit for bit."""
+    K, N, group = 2048, 776, 128
+    case = workloads.make_case(M, K, N, group, seed=177 + M)
+    ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], None, group)
+    plan = B.Plan(kernel=4, split_k=split_k, tile=tile)
+    first = run_gemm(B, case, group, plan)
+    again = run_gemm(B, case, group, plan)
+    assert_within_band(first, ref, f"mid-batch split={split_k} M={M} tile={tile}")
+    assert np.array_equal(first.view(np.uint16), again.view(np.uint16))
+
+
+def test_mid_batch_request_falls_back_when_unsupported(B):
+    # act-order, K or group sizes that are not multiples of 64, more than 128 rows: served by the other kernels
+    for M, K, N, group, act in [(40, 512, 136, 32, False), (40, 160, 136, 32, False), (40, 512, 136, 128, True),
+                                (200, 512, 136, 128, False)]:
+        assert B.gptq_w4a16_plan_query(M, K, N, group, act, B.Plan(kernel=4)).kernel != 4
+        case = workloads.make_case(M, K, N, group, seed=M + N, act_order=act)
+        ref = oracle.gemm_ref(case["x"], case["qweight"], case["qzeros"], case["scales"], case["g_idx"], group)
+        out = run_gemm(B, case, group, B.Plan(kernel=4))
+        assert_within_band(out, ref, f"fallback M={M} g={group} act={act}")
+
+
 # ------------------------------------------------------------------ exactness pins in the GEMM kernels themselves
 
-@pytest.mark.parametrize("M,plan_kernel", [(1, 1), (4, 1), (8, 1), (16, 1), (40, 2), (300, 2), (8, 3), (24, 3), (40, 3), (64, 3)])
+@pytest.mark.parametrize("M,plan_kernel", [(1, 1), (4, 1), (8, 1), (16, 1), (40, 2), (300, 2), (8, 3), (24, 3), (40, 3), (64, 3),
+                                           (20, 4), (48, 4), (100, 4)])
 @pytest.mark.parametrize("act", [False, True])
 def test_one_hot_rows_return_weight_rows_bit_exact(B, M, plan_kernel, act):
     K, N, group = 1024, 264, 128
@@ -328,7 +383,7 @@ def test_one_hot_rows_return_weight_rows_bit_exact(B, M, plan_kernel, act):
         assert np.array_equal(out[m].view(np.uint16), w16[j].view(np.uint16)), f"row {m} (k={j})"
 
 
-@pytest.mark.parametrize("M", [1, 8, 64])
+@pytest.mark.parametrize("M", [1, 8, 64, 100, 200])
 def test_dyadic_scales_and_ternary_activations_are_exact(B, M):
     # scales 2^-7, x in {-1,0,1}: every partial sum is an exact dyadic rational, so fp32 accumulation in any
     # order equals the fp64 reference and the fp16 result is its single rounding
@@ -350,7 +405,7 @@ def test_codes_equal_to_zero_points_give_zero(B, M):
             "x": workloads.make_activations(M, K, seed=4)}
     out = run_gemm(B, case, group)
     if M > 1:
-        # exact q - z before the contraction (small-batch and big-tile MFMA kernels): every product is exactly zero
+        # exact q - z before the contraction (all three MFMA kernels): every product is exactly zero
         assert np.all(out == 0)
     else:
         # the single-row vector kernel contracts the biased codes (1024 + q) and takes the bias and the zero
@@ -536,6 +591,7 @@ def test_other_group_sizes_including_one_group_per_column(B, M, group):
     (1, 2816, 520, dict(kernel=1, split_k=4, tile=32)),   # vector kernel, K slices through scratch
     (8, 2048, 328, dict(kernel=3, split_k=3)),            # small-batch MFMA kernel, K slices
     (96, 1408, 288, dict(kernel=2, tile=5, split_k=3)),   # big-tile kernel, K slices
+    (48, 1408, 288, dict(kernel=4, split_k=3)),           # mid-batch streaming kernel, K slices
     (1, 1024, 264, dict()),                                # default dispatch
 ])
 def test_graph_replays_match_eager(B, M, K, N, plan_args):
@@ -583,17 +639,17 @@ def test_captured_graph_survives_scratch_growth(B):
         torch.cuda.synchronize()
         assert np.array_equal(out.cpu().numpy().view(np.uint16), eager.view(np.uint16))
         # 5 K slices x 96 tiles x 64 x 128 fp32 = 15.7 MB of partial sums: more than the first block holds
-        big_plan = B.gptq_w4a16_plan_query(64, 4096, 12288, group)
-        assert big_plan.kernel == 2 and big_plan.split_k * 96 * 64 * 128 * 4 > 8 << 20
+        big_plan = B.Plan(kernel=2, tile=5, split_k=5)
+        assert B.gptq_w4a16_plan_query(64, 4096, 12288, group, False, big_plan).split_k == 5
         big = workloads.make_case(64, 4096, 12288, group, seed=32)
-        run_gemm(B, big, group)
+        run_gemm(B, big, group, big_plan)
         junk = torch.full((16 << 20,), -1, dtype=torch.int32, device="cuda")  # would land in a freed block
         for rep in range(3):
             out.fill_(float("nan"))
             graph.replay()
             torch.cuda.synchronize()
             assert np.array_equal(out.cpu().numpy().view(np.uint16), eager.view(np.uint16)), f"replay {rep} after growth"
-            run_gemm(B, big, group)
+            run_gemm(B, big, group, big_plan)
         del junk
 
 
@@ -602,6 +658,7 @@ def test_scratch_growth_is_refused_under_capture(B):
     B.gptq_w4a16_set_workspace(None)
     run_gemm(B, workloads.make_case(1, 1024, 264, group, seed=1), group)  # first block: 8 MiB
     big = workloads.make_case(64, 4096, 12288, group, seed=32)
+    big_plan = B.Plan(kernel=2, tile=5, split_k=5)  # 15.7 MB of partial sums
     x, qw, qz, sc = (dev(big[k]) for k in ("x", "qweight", "qzeros", "scales"))
     out = torch.zeros((64, 12288), dtype=torch.float16, device="cuda")
     stream = torch.cuda.Stream()
@@ -611,12 +668,12 @@ def test_scratch_growth_is_refused_under_capture(B):
         with torch.cuda.graph(graph, stream=stream):
             out.zero_()
             try:
-                B.gptq_w4a16_gemm(x, qw, qz, sc, None, out, group)
+                B.gptq_w4a16_gemm(x, qw, qz, sc, None, out, group, big_plan)
             except B.GptqError as e:
                 code = e.code
         torch.cuda.synchronize()
     assert code == -5, "growing the scratch while the stream is captured must be refused"
-    got = run_gemm(B, big, group)  # eagerly it grows and works
+    got = run_gemm(B, big, group, big_plan)  # eagerly it grows and works
     rng = np.random.default_rng(3)
     mi = rng.integers(0, 64, 256).astype(np.int32)
     ni = rng.integers(0, 12288, 256).astype(np.int32)
@@ -644,6 +701,8 @@ def test_act_order_table_too_large_for_lds_falls_back(B):
     (8, 2048, 1024, dict(kernel=3, tile=256)),
     (32, 2048, 1024, dict(kernel=3, tile=256, split_k=2)),
     (96, 2048, 520, dict(kernel=2)),
+    (48, 2048, 520, dict(kernel=4)),
+    (100, 2048, 520, dict(kernel=4, split_k=2)),
 ])
 @pytest.mark.parametrize("kind", ["offset", "outliers", "huge_offset"])
 def test_activations_with_large_mean_and_outliers(B, M, K, N, plan_args, kind):

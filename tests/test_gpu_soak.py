@@ -1,5 +1,5 @@
 """Bounded soak of the K-slice exchange (GPU): a few thousand launches that cycle through the K-split paths of all
-three GEMM kernels over changing shapes, every result compared bit for bit with the first result of its case.
+four GEMM kernels over changing shapes, every result compared bit for bit with the first result of its case.
 
 The exchange of partial sums between workgroups rests on write-through stores, an acknowledged-store wait and an
 arrival counter (see csrc/exchange.h); a lost or stale partial sum would show as a changed output bit.  The run
@@ -27,8 +27,10 @@ CASES = [
     (16, 4096, 4096, False, dict()),                              # small-batch kernel, automatic plan (4 slices)
     (48, 4096, 1024, False, dict(kernel=3, tile=64, split_k=2)),
     (64, 4096, 1024, False, dict(kernel=2, tile=5, split_k=8)),
+    (56, 4096, 1024, False, dict(kernel=4, tile=64, split_k=4)),
+    (120, 2048, 544, False, dict(kernel=4, split_k=3)),
     (100, 2048, 544, False, dict(kernel=2, tile=3, split_k=2)),
-    (64, 4096, 4096, False, dict()),                              # big-tile kernel, automatic plan with K slices
+    (64, 4096, 4096, False, dict()),                              # mid-batch kernel, automatic plan with K slices
 ]
 ROUNDS = 1500
 BUDGET_S = 25.0

@@ -70,11 +70,11 @@ def test_static_matches_regular_twice_in_a_row(B, first, second):
 
 
 def test_static_rejects_a_problem_beyond_its_block(B):
-    # automatic plan: small-batch kernel with 10 K slices of 32 x 57344 fp32 partial sums = 73 MB > 32 MiB.
+    # automatic plan: small-batch kernel with 8 K slices of 16 x 131072 fp32 partial sums = 64 MiB > 48 MiB.
     # The call returns before anything is enqueued, so the pointers only have to be non-null and aligned.
-    M, K, N, group = 32, 8192, 57344, 128
+    M, K, N, group = 16, 8192, 131072, 128
     plan = B.gptq_w4a16_plan_query(M, K, N, group, False)
-    assert plan.split_k * M * N * 4 > 32 << 20
+    assert plan.split_k * M * N * 4 > 48 << 20
     buf = torch.zeros(1024, dtype=torch.int32, device="cuda")
     p = ctypes.c_void_p(buf.data_ptr())
     rc = B.load().gptq_w4a16_gemm_static(p, p, p, p, None, p, M, K, N, group, None)
