@@ -247,7 +247,7 @@ def graph_us(torch, launches, reps=4, batches=3):
 
 def sweep_tables(torch, B, workloads, layers):
     """Side tables (not the headline): the decode and mid batch sweep on the Llama-7B shapes, the act-order layer with
-    its g_idx kernels and repacked, and the Llama-70B shapes at M = 1 and 16.  Every launch streams its weights from
+    its g_idx kernels and repacked, and the Llama-70B shapes at M = 1, 16 and 64.  Every launch streams its weights from
     HBM (the launches of a graph rotate over distinct weight copies larger than the caches).  Per shape also:
     `read_probe`, a plain read kernel over the same packed-weight buffers timed the same way (what any kernel of
     that footprint pays for launch, latency and ramp), and `vector_dot`, the single-row kernel with its inner loop
@@ -274,6 +274,15 @@ def sweep_tables(torch, B, workloads, layers):
         row["vector_dot M=1"] = [round(us, 2), round(algorithmic_bytes(1, sh.K, sh.N) / us / 1e3)]
         us = graph_us(torch, [(lambda t=mats[si]: B.gptq_w4a16_stream_probe(t["qweight"], sink)) for mats in layers])
         row["read_probe"] = [round(us, 2), round(sh.K * sh.N // 2 / us / 1e3)]
+        # the three MFMA kernels side by side at 64 rows (explicit plans; the automatic one is in "M=64")
+        x = torch.randn((64, sh.K), device="cuda").half()
+        o = torch.empty((64, sh.N), dtype=torch.float16, device="cuda")
+        side = {}
+        for name, kid in (("mid_batch", 4), ("big_tile", 2), ("small_batch", 3)):
+            plan = B.Plan(kernel=kid)
+            side[name] = round(graph_us(torch, [(lambda t=mats[si]: B.gptq_w4a16_gemm(
+                x, t["qweight"], t["qzeros"], t["scales"], None, o, GROUP, plan)) for mats in layers], batches=1), 2)
+        row["kernels at M=64"] = side
         out["llama7b"].append(row)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(1234)
@@ -327,7 +336,7 @@ def sweep_tables(torch, B, workloads, layers):
         copies = max(2, int(1.3e9 // (sh.K * sh.N // 2)) + 1)
         qws, qz, sc = device_weights(torch, sh.K, sh.N, copies, gen)
         row = {"shape": f"{sh.name} K={sh.K} N={sh.N}"}
-        for M in (1, 16):
+        for M in (1, 16, 64):
             x = torch.randn((M, sh.K), device="cuda").half()
             o = torch.empty((M, sh.N), dtype=torch.float16, device="cuda")
             us = graph_us(torch, [(lambda q=q: B.gptq_w4a16_gemm(x, q, qz, sc, None, o, GROUP)) for q in qws])
