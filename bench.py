@@ -380,8 +380,8 @@ def measured_traffic(key):
 
 def context_lines(torch, B):
     """What the box itself achieves, as context for the roofline fractions: a device copy, the dense fp16 matmul of
-    the vendor library on the prefill shape, and the matrix pipe alone (MFMA-only loop on random register operands,
-    no memory traffic) under the same power budget."""
+    the vendor library on the prefill shape, the matrix pipe alone (MFMA-only loop on random register operands,
+    no memory traffic) under the same power budget, and the price of vector instructions beside an MFMA."""
     n = 256 * 1024 * 1024
     src = torch.empty(n, dtype=torch.int32, device="cuda").random_()
     dst = torch.empty_like(src)
@@ -403,6 +403,20 @@ def context_lines(torch, B):
 
     sec = timed_launches(torch, probe)
     mfma_only = flops[0] / sec / 1e12
+    # what vector work beside an MFMA costs: ns per (one 32x32x16 MFMA + V packed-fp16 instructions) per SIMD,
+    # with one and with two wavefronts per SIMD
+    issue = {}
+    for waves in (1, 2):
+        row = {}
+        for v in (0, 4, 8, 12, 16):
+            count = [0.0]
+
+            def group():
+                count[0] = B.gptq_w4a16_issue_probe(ops, sink, 1000, v, waves)
+
+            sec = timed_launches(torch, group, min_warm_s=0.03, min_timed_s=0.02)
+            row[f"V={v}"] = round(sec * 1e9 / count[0], 2)
+        issue[f"{waves} wavefront(s) per SIMD"] = row
     props = torch.cuda.get_device_properties(0)
     device = {"name": props.name, "arch": getattr(props, "gcnArchName", ""), "compute_units": props.multi_processor_count,
               "memory_GiB": round(props.total_memory / 2**30, 1)}
@@ -411,7 +425,8 @@ def context_lines(torch, B):
         device["max_clock_MHz"] = round(clock_khz / 1e3)
     return {"device": device, "device_copy_GBps_read_plus_write": round(copy_gbs, 1),
             "torch_matmul_fp16_dense_TFLOPs_M2048_K4096_N22016": round(dense, 1),
-            "mfma_only_loop_random_operands_TFLOPs": round(mfma_only, 1)}
+            "mfma_only_loop_random_operands_TFLOPs": round(mfma_only, 1),
+            "ns_per_mfma_with_V_vector_instructions": issue}
 
 
 def timed_launches(torch, fn, min_warm_s=0.06, min_timed_s=0.03):

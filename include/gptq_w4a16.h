@@ -244,6 +244,19 @@ GPTQ_API int gptq_w4a16_stream_probe(const void *buf, size_t bytes, void *sink, 
 GPTQ_API int gptq_w4a16_mfma_probe(const void *operands, size_t bytes, void *sink, int iters, double *flops,
                                    gptq_stream_t stream);
 
+/*
+ * gptq_w4a16_issue_probe: on every compute unit, one after the other, four workgroups of 4 * waves_per_simd
+ * wavefronts (waves_per_simd = 1, 2 or 4) run `iters` x 4 groups of one v_mfma_f32_32x32x16_f16 followed by
+ * valu_per_mfma (0, 2, 4, 6, 8, 12 or 16) independent packed-fp16 vector instructions, on register operands read
+ * once from `operands` (device, 16-byte aligned, `bytes` long; random fp16 values are the representative case).
+ * *mfma_per_simd (host, may be NULL) receives the number of MFMAs each SIMD executes, so that the caller's own
+ * timing gives the time per MFMA per SIMD: what vector work beside an MFMA costs on this chip.  `sink`: device,
+ * >= 4 bytes, 16-byte aligned, written at most once.  Errors: GPTQ_INVALID_ARG (null pointer, iters outside
+ * [1, 2^20], a count not listed), GPTQ_MISALIGNED, GPTQ_HIP_ERROR.
+ */
+GPTQ_API int gptq_w4a16_issue_probe(const void *operands, size_t bytes, void *sink, int iters, int valu_per_mfma,
+                                    int waves_per_simd, double *mfma_per_simd, gptq_stream_t stream);
+
 /* Text for a status code (static storage). */
 GPTQ_API const char *gptq_w4a16_strerror(int code);
 

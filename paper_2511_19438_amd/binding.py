@@ -36,7 +36,7 @@ class Plan(ctypes.Structure):
 EXPORTS = ("gptq_w4a16_gemm", "gptq_w4a16_gemm_static", "gptq_w4a16_gemm_plan", "gptq_w4a16_plan_query", "gptq_w4a16_act_order_prepare",
            "gptq_w4a16_gemm_prepared", "gptq_w4a16_shift_zeros", "gptq_w4a16_dequant", "gptq_w4a16_unpack",
            "gptq_w4a16_workspace_bytes", "gptq_w4a16_set_workspace", "gptq_w4a16_strerror", "gptq_w4a16_version",
-           "gptq_w4a16_stream_probe", "gptq_w4a16_mfma_probe")
+           "gptq_w4a16_stream_probe", "gptq_w4a16_mfma_probe", "gptq_w4a16_issue_probe")
 
 
 def load() -> ctypes.CDLL:
@@ -78,6 +78,8 @@ def load() -> ctypes.CDLL:
     lib.gptq_w4a16_stream_probe.restype = ci
     lib.gptq_w4a16_mfma_probe.argtypes = [vp, ctypes.c_size_t, vp, ci, ctypes.POINTER(ctypes.c_double), vp]
     lib.gptq_w4a16_mfma_probe.restype = ci
+    lib.gptq_w4a16_issue_probe.argtypes = [vp, ctypes.c_size_t, vp, ci, ci, ci, ctypes.POINTER(ctypes.c_double), vp]
+    lib.gptq_w4a16_issue_probe.restype = ci
     lib.gptq_w4a16_version.argtypes = []
     lib.gptq_w4a16_version.restype = ci
     _lib = lib
@@ -265,3 +267,16 @@ def gptq_w4a16_mfma_probe(operands: torch.Tensor, sink: torch.Tensor, iters: int
     if rc != 0:
         raise GptqError(rc, "gptq_w4a16_mfma_probe")
     return float(flops.value)
+
+
+def gptq_w4a16_issue_probe(operands: torch.Tensor, sink: torch.Tensor, iters: int, valu_per_mfma: int,
+                           waves_per_simd: int) -> float:
+    """One MFMA + `valu_per_mfma` independent packed-fp16 instructions per group, `waves_per_simd` wavefronts per
+    SIMD; returns the number of MFMAs each SIMD executes in the launch."""
+    count = ctypes.c_double(0.0)
+    rc = load().gptq_w4a16_issue_probe(_ptr(operands, torch.float16, "operands"), operands.numel() * 2,
+                                       ctypes.c_void_p(sink.data_ptr()), int(iters), int(valu_per_mfma),
+                                       int(waves_per_simd), ctypes.byref(count), _stream())
+    if rc != 0:
+        raise GptqError(rc, "gptq_w4a16_issue_probe")
+    return float(count.value)

@@ -27,7 +27,7 @@ def declared_functions():
 
 def test_header_declares_the_expected_entry_points():
     names = declared_functions()
-    assert len(names) == len(set(names)) == 15
+    assert len(names) == len(set(names)) == 16
     for required in ("gptq_w4a16_gemm", "gptq_w4a16_dequant", "gptq_w4a16_unpack", "gptq_w4a16_workspace_bytes",
                      "gptq_w4a16_set_workspace", "gptq_w4a16_strerror", "gptq_w4a16_version",
                      "gptq_w4a16_gemm_plan", "gptq_w4a16_plan_query", "gptq_w4a16_act_order_prepare",

@@ -762,3 +762,21 @@ def test_single_row_group_level_correction(B, K, N, tile):
         plan = B.Plan(kernel=1, tile=tile, split_k=1) if tile else None
         out = run_gemm(B, case, group, plan)
         assert_within_band(out, ref, f"single row K={K} N={N} tile={tile} g={group}")
+
+
+# ------------------------------------------------------------------ measurement aids
+
+def test_measurement_aids_run_and_validate_their_arguments(B):
+    ops = (torch.rand(1 << 12, device="cuda") * 2.0 - 1.0).half()
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    buf = torch.zeros(1 << 20, dtype=torch.int32, device="cuda")
+    B.gptq_w4a16_stream_probe(buf, sink.view(torch.int32))
+    assert B.gptq_w4a16_mfma_probe(ops, sink, 10) > 0
+    for waves in (1, 2, 4):
+        for v in (0, 2, 4, 6, 8, 12, 16):
+            assert B.gptq_w4a16_issue_probe(ops, sink, 5, v, waves) == 4 * waves * 5 * 4
+    torch.cuda.synchronize()
+    for v, waves, iters in ((3, 2, 5), (4, 3, 5), (4, 2, 0)):
+        with pytest.raises(B.GptqError) as err:
+            B.gptq_w4a16_issue_probe(ops, sink, iters, v, waves)
+        assert err.value.code == -1

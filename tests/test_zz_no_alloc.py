@@ -51,11 +51,13 @@ def both(B, M, K, N, group, act, seed):
 
 
 # (first call, second smaller call); every first call needs split-K scratch under the automatic plan:
-# vector kernel, small-batch MFMA kernel, big-tile MFMA kernel with K slices, act-order lookup kernel
+# vector kernel, small-batch MFMA kernel, mid-batch MFMA kernel, big-tile MFMA kernel with K slices, act-order
+# lookup kernel
 PAIRS = [
     ((1, 11008, 4096, 128, False), (1, 4096, 520, 128, False)),
     ((8, 4096, 1024, 128, False), (3, 2048, 264, 128, False)),
     ((64, 4096, 1024, 128, False), (40, 2048, 520, 128, False)),
+    ((200, 4096, 1024, 128, False), (130, 2048, 520, 128, False)),
     ((4, 4096, 1032, 128, True), (1, 1024, 264, 128, True)),
 ]
 
