@@ -254,18 +254,27 @@ __global__ __launch_bounds__(64 * WAVES) void mid_kernel(const Args a)
             ss[t] = live ? (sb | (sb << 16)) : 0u;
         }
         const unsigned char *xs = ring + (size_t)buf * XBUF;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            half8_t av[TMB];
+        // The A operands of a step are read from LDS while the MFMAs of the step before run (two register sets):
+        // issued right before their use, the read's latency stalled the wavefront once per step.
+        half8_t av[2][TMB];
+        auto read_a = [&](int s, half8_t (&dst)[TMB]) {
 #pragma unroll
             for (int i = 0; i < TMB; ++i)
-                av[i] = *reinterpret_cast<const half8_t *>(xs + (aoff ^ (uint32_t)(s << 5)) + i * 4096);
+                dst[i] = *reinterpret_cast<const half8_t *>(xs + (aoff ^ (uint32_t)(s << 5)) + i * 4096);
+        };
+        read_a(0, av[0]);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            if (s + 1 < 4) {
+                read_a(s + 1, av[(s + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);  // (keeps the reads above the arithmetic below)
+            }
 #pragma unroll
             for (int t = 0; t < NB; ++t) {
                 const half8_t b = dequant_word(r.w[s][t], magic, nz[t], ss[t]);  // (vector element t)
 #pragma unroll
                 for (int i = 0; i < TMB; ++i)
-                    acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[i], b, acc[i][t], 0, 0, 0);
+                    acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[s & 1][i], b, acc[i][t], 0, 0, 0);
             }
         }
     };

@@ -245,3 +245,31 @@ def test_big_tile_plan_is_well_formed_for_every_shape(lib):
     # few output tiles and a deep K: slices; many tiles: none
     assert binding.gptq_w4a16_plan_query(64, 11008, 4096, 128).split_k > 1
     assert binding.gptq_w4a16_plan_query(2048, 4096, 22016, 128).split_k == 1
+
+
+def test_mid_batch_plan_is_well_formed_for_every_shape(lib):
+    """The mid-batch kernel's automatic plan: 64- or 128-column tiles (64 with more than 64 rows), one workgroup per
+    compute unit at most once K is split, every wavefront keeps at least 128 k, slices cover K, and the scratch of
+    the slices is covered by the workspace bound wherever the default dispatch runs the kernel."""
+    from paper_2511_19438_amd import binding, workloads
+
+    shapes = [(s.K, s.N) for s in workloads.LLAMA_7B + workloads.LLAMA_70B] + [(64, 8), (512, 264), (4096, 11008)]
+    for (K, N) in shapes:
+        for M in (1, 17, 32, 33, 64, 65, 128):
+            pl = binding.gptq_w4a16_plan_query(M, K, N, 64, plan=binding.Plan(kernel=4))
+            assert pl.kernel == 4 and pl.tile in (64, 128), (M, K, N, pl.tile)
+            assert pl.tile == 64 or M <= 64
+            tiles = -(-N // pl.tile)
+            assert 1 <= pl.split_k <= max(1, K // 64)
+            if pl.split_k > 1:
+                assert tiles * pl.split_k <= 256, (M, K, N, pl.split_k)
+                assert K // pl.split_k >= 8 * 128 or pl.split_k == 1, (M, K, N, pl.split_k)
+            auto = binding.gptq_w4a16_plan_query(M, K, N, 64)
+            if auto.kernel == 4 and auto.split_k > 1:
+                assert lib.gptq_w4a16_workspace_bytes(M, K, N, 64) >= auto.split_k * M * N * 4
+            # an explicit slice count is honoured (up to one slice per 64-k stage)
+            asked = binding.gptq_w4a16_plan_query(M, K, N, 64, plan=binding.Plan(kernel=4, split_k=3))
+            assert asked.split_k == min(3, K // 64) or (K // 64) % 3 != 0 and asked.split_k <= 3
+    # wide layers: no split; narrow and deep ones: slices
+    assert binding.gptq_w4a16_plan_query(64, 4096, 22016, 128).split_k == 1
+    assert binding.gptq_w4a16_plan_query(64, 11008, 4096, 128).split_k > 1
