@@ -121,7 +121,7 @@ typedef struct gptq_w4a16_plan {
     int split_k;     /* number of K slices (all four kernels; the big-tile kernel splits by itself on every tile
                         but 256x256); 0 auto */
     int tile;        /* vector kernel: columns per workgroup (16, 32, 64, 128 or 256);
-                        small-batch MFMA kernel: columns per workgroup (64 or 256; anything else = auto);
+                        small-batch MFMA kernel: columns per workgroup (64, 128 - up to 32 rows - or 256; anything else = auto);
                         mid-batch MFMA kernel: columns per workgroup (64 or 128; anything else = auto; more than
                         64 rows always use 64);
                         MFMA kernel: tile id = rows x columns per workgroup (wavefront grid):

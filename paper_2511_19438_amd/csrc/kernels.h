@@ -63,7 +63,8 @@ bool decode_ablation_supported(const Problem &p);
 // ---- small batch: MFMA kernel with the vector kernel's split-K decomposition, M <= 128 (64 rows per launch) ----
 constexpr int kSkinnyMaxM = 128;
 struct SkinnyPlan {
-    int cols_per_wg;      // 64 (wavefronts split the K slice) or 256 (wavefronts side by side); 0 = choose
+    int cols_per_wg;      // 64 (wavefronts split the K slice), 128 (two column blocks, four wavefronts each split the slice)
+                          // or 256 (four wavefronts side by side); 0 = choose
     int split_k;          // number of K slices (0 = choose)
     int units_per_slice;  // 128-k units per slice
 };

@@ -31,6 +31,8 @@ int rows_of_launch(int M)
 // Wavefronts per workgroup: eight where the 64-column workgroups have a compute unit each, else four.
 int waves_of(int tiles_n, int split_k, int wn, int tm)
 {
+    if (wn == 2)
+        return 8;  // 128-column workgroups: two column blocks of four wavefronts
     // (four row blocks do not fit the 256 registers that two wavefronts per SIMD leave each)
     return (wn == 1 && tm <= 2 && (long long)tiles_n * split_k <= 256) ? 8 : 4;
 }
@@ -69,14 +71,20 @@ void skinny_make_plan(const Problem &p, SkinnyPlan &plan)
     const int total_units = p.K / skinny::kUnitK;
     if (p.group_size < skinny::kUnitK)
         plan.cols_per_wg = 64;  // the small-group variants exist for the 64-column workgroup
-    if (plan.cols_per_wg != 64 && plan.cols_per_wg != 256) {
+    const bool wide_ok = rows <= 32;  // the 128-column workgroup exists for one and two row blocks
+    if (plan.cols_per_wg == 128 && !wide_ok)
+        plan.cols_per_wg = 0;
+    if (plan.cols_per_wg != 64 && plan.cols_per_wg != 128 && plan.cols_per_wg != 256) {
         // Wide tiles stage the activations once for four times as many weights, but a workgroup's wavefronts
         // then walk the whole slice: that only pays (measured) once the columns alone spread over most of
-        // the chip.
-        plan.cols_per_wg = ceil_div(p.N, 256) >= 192 ? 256 : 64;
+        // the chip.  In between - more 64-column tiles than compute units, but no more 128-column ones - two
+        // column blocks share a workgroup of eight wavefronts, so that every compute unit has one workgroup
+        // instead of some having two.
+        const int tiles64 = ceil_div(p.N, 64);
+        plan.cols_per_wg = ceil_div(p.N, 256) >= 192 ? 256 : (wide_ok && tiles64 > 256 && ceil_div(p.N, 128) <= 256) ? 128 : 64;
     }
     // where the activations of a slice are staged in LDS (wide tiles, more than 32 rows) they must fit
-    const bool direct = plan.cols_per_wg == 64;
+    const bool direct = plan.cols_per_wg <= 128;
     int max_units = direct ? total_units : kMaxActivationLdsBytes / (rows * 2) / skinny::kUnitK;
     if (max_units < 1)
         max_units = 1;
@@ -112,7 +120,8 @@ void skinny_make_plan(const Problem &p, SkinnyPlan &plan)
         if (split < 1)
             split = 1;
         // narrow tiles: one unit per wavefront and turn
-        const int quantum = plan.cols_per_wg == 64 ? waves_of(tiles_n, split, 1, row_blocks(launch_m)) : 1;
+        const int quantum = plan.cols_per_wg == 64 ? waves_of(tiles_n, split, 1, row_blocks(launch_m))
+                                                   : plan.cols_per_wg == 128 ? 4 : 1;
         ups = ceil_div(ceil_div(total_units, split), quantum) * quantum;
         if (ups > total_units)
             ups = total_units;
@@ -161,8 +170,8 @@ hipError_t launch_skinny(const Problem &p, const SkinnyPlan &plan, void *workspa
 
         const int tm = row_blocks(a.M);
         const int rows = 16 * tm;
-        // 64-column workgroups read the activations straight from global memory
-        const bool direct = wn == 1;
+        // 64- and 128-column workgroups read the activations straight from global memory
+        const bool direct = wn <= 2;
         const size_t xs = direct ? 0 : (size_t)rows * plan.units_per_slice * skinny::kUnitK * sizeof(half_t);
         const int waves = waves_of(a.tiles_n, a.split_k, wn, tm);
         const size_t red = (size_t)waves * rows * skinny::kCols * sizeof(float);  // [waves/wn][rows][64*wn]
@@ -178,6 +187,10 @@ hipError_t launch_skinny(const Problem &p, const SkinnyPlan &plan, void *workspa
             else
                 err = waves == 8 ? (tm == 1 ? launch_tm<1, 1, 8, 4>(a, lds, stream) : launch_tm<2, 1, 8, 4>(a, lds, stream))
                                  : (tm == 1 ? launch_tm<1, 1, 4, 4>(a, lds, stream) : launch_tm<2, 1, 4, 4>(a, lds, stream));
+        } else if (wn == 2) {
+            if (tm > 2)
+                return hipErrorInvalidValue;  // refused by skinny_make_plan
+            err = tm == 1 ? launch_tm<1, 2, 8>(a, lds, stream) : launch_tm<2, 2, 8>(a, lds, stream);
         } else if (wn == 4)
             err = tm == 1 ? launch_tm<1, 4, 4>(a, lds, stream)
                           : tm == 2 ? launch_tm<2, 4, 4>(a, lds, stream) : launch_tm<4, 4, 4>(a, lds, stream);

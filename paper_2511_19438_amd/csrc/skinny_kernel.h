@@ -88,7 +88,7 @@ struct UnitRegs {                // GPU: quantisation groups per unit (1: groups
     u32x4_t xa[XROWS > 0 ? XROWS : 1][4];  // A operand per row block and k step
 };
 
-// TM: 16-row blocks (M <= 16 * TM).  WN: wavefronts side by side along N (1 or 4).  With WN = 1 the
+// TM: 16-row blocks (M <= 16 * TM).  WN: wavefronts side by side along N (1, 2 or 4).  With WN = 1 the
 // workgroup owns 64 columns and its four wavefronts split the K slice (narrow layers: many small
 // workgroups); with WN = 4 it owns 256 columns, every wavefront walks the whole slice for its own 64
 // columns and the staged activations serve four times as many weights (wide layers).
@@ -106,7 +106,8 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
 {
     static_assert(GPU == 1 || GPU == 2 || GPU == 4, "groups of >= 128, 64 or 32 k");
     static_assert(GPU == 1 || TM <= 2, "small groups: up to two row blocks");
-    static_assert(WAVES == 4 || (WAVES == 8 && WN == 1), "eight wavefronts only where they split the slice");
+    static_assert(WAVES == 4 || (WAVES == 8 && WN <= 2), "eight wavefronts only where they split the slice");
+    static_assert(WN != 2 || WAVES == 8, "128-column workgroups: two column blocks x four wavefronts each");
     constexpr int kWaves = WAVES;
     constexpr int kThreads = 64 * WAVES;
     constexpr int ROWS = 16 * TM;
@@ -116,7 +117,9 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_kernel(const Args a)
     // slice), so staging them in LDS would be a copy without reuse: each lane loads its A operand straight
     // from global memory (L2), in the same pipeline as the weights.  With 256-column workgroups the four
     // wavefronts share the slice and the activations are staged once in LDS.
-    constexpr bool DIRECT = WN == 1;
+    // (128-column workgroups, WN = 2 with eight wavefronts, read them the same way: every activation is then
+    // loaded by the two wavefronts that share its k range, from L2.)
+    constexpr bool DIRECT = WN <= 2;
     // DIRECT with four row blocks: the A operands of two units in flight would take 128 registers.  They are kept
     // for ONE unit instead and refilled step by step: as soon as a 32-k step's operands have been permuted into
     // the MFMA's k order, the same registers receive that step of the NEXT unit (from L2: a four-step lead is

@@ -258,7 +258,7 @@ SKINNY_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("tile", [64, 256])
+@pytest.mark.parametrize("tile", [64, 128, 256])
 @pytest.mark.parametrize("M", [1, 5, 8, 16, 17, 32, 33, 49, 64, 65, 100, 128])
 @pytest.mark.parametrize("K,N,group", SKINNY_SHAPES)
 def test_small_batch_mfma_kernel_matches_oracle(B, M, K, N, group, tile):
@@ -268,7 +268,7 @@ def test_small_batch_mfma_kernel_matches_oracle(B, M, K, N, group, tile):
     assert_within_band(out, ref, f"small-batch M={M} K={K} N={N} g={group} tile={tile}")
 
 
-@pytest.mark.parametrize("tile", [64, 256])
+@pytest.mark.parametrize("tile", [64, 128, 256])
 @pytest.mark.parametrize("split_k", [1, 2, 3, 5, 16])
 @pytest.mark.parametrize("M", [8, 40, 64, 90])
 def test_small_batch_mfma_kernel_splits(B, split_k, M, tile):
